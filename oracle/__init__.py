@@ -1,0 +1,36 @@
+"""CPU oracle for ragged chunked-prefill attention with a persistent KV cache.
+
+TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this
+package: only tests, the smoke check and the benchmark's CPU-baseline leg use
+it.  It shares no code with the HIP library and never imports it.
+
+What it states (float64 throughout, inputs are bf16 bit patterns widened
+exactly):
+  * attention.py  - softmax(s * Q K^T + causal mask) V written out as the plain
+                    definition, for arbitrary query positions (so one-shot
+                    prefill, a streamed chunk, or single sampled rows are all
+                    the same function with different position lists);
+  * kv_cache.py   - the per-sequence cache that persists across chunks
+                    (Sec. 3.1: the scorer processes chunk k-1 on top of the
+                    chunks before it) and the streamed episode built on it;
+  * schedule.py   - which rows exist at each pass of the streaming loop
+                    (Alg. 1, generation loop; Sec. 3.1).
+
+Pins (tests/test_oracle_*.py): brute-force triple loop on tiny inputs, a
+hand-derived two/three-token example with rational softmax weights
+(tests/golden), closed forms (V==1, Q==0 -> running mean, first token,
+dominant key), the streaming-equivalence invariant of Sec. 3.1 / Eq. 3 (any
+chunking equals one-shot prefill, cache included), causality under
+perturbation of future tokens, GQA / batch-permutation / V-linearity
+invariants, and an independent float64 library routine.  The append is pinned
+by a full-buffer compare against a numpy scatter with sentinels.  No function
+here is "parity unpinned".
+"""
+from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
+from .kv_cache import KVCacheOracle, CapacityError, stream_episode
+from .schedule import chunk_schedule, num_steps
+
+__all__ = [
+    "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
+    "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
+]
