@@ -1,0 +1,187 @@
+/*
+ * oppo_attn.h - C ABI of the chunked-prefill attention library for MI355X (gfx950).
+ *
+ * The computation is the scorer's side of OPPO's intra-step overlap (Sec. 3.1 of
+ * arXiv 2509.25762): while the actor is still decoding, the reward/critic model
+ * prefills the response chunk by chunk.  For one attention layer that is, per
+ * pass of the streaming loop (Alg. 1, generation loop) and per unfinished
+ * sequence:
+ *   1. append the chunk's K/V rows to the sequence's persistent cache, and
+ *   2. let the chunk's query rows attend causally to the cached prefix plus the
+ *      chunk itself.
+ * Streaming must not change any result (Sec. 3.1, Eq. 3): any chunking gives the
+ * outputs and the cache of a one-shot prefill.
+ *
+ * Conventions shared by every entry point
+ *   - bf16 tensors are raw 16-bit patterns; "device" pointers are HIP device
+ *     memory valid on the current device, "host" pointers ordinary host memory.
+ *   - Length arrays are HOST memory and are snapshotted during the call: the
+ *     caller may overwrite them as soon as the call returns, although the
+ *     kernels run later on the stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise and never allocate device
+ *     memory.  All device buffers, the workspace included, belong to the caller
+ *     and must stay alive until the enqueued work has run.
+ *   - Return value: OPPO_OK or a negative oppo_status.  Every argument check
+ *     happens on the host before anything is enqueued, so a failed call has
+ *     written nothing and changed no length.  oppo_last_error() gives a
+ *     human-readable reason (thread-local storage, valid until the next failing
+ *     call on the same thread).
+ *   - GQA: q-head h reads kv-head h / (num_q_heads / num_kv_heads).
+ *   - Token-major layouts: a tensor [rows][H][D] stores row r, head h, element d
+ *     at (r * H + h) * D + d.
+ */
+#ifndef OPPO_ATTN_H
+#define OPPO_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OPPO_OK = 0,
+  OPPO_ERR_INVALID = -1,     /* null pointer, negative size, inconsistent lengths   */
+  OPPO_ERR_UNSUPPORTED = -2, /* head_dim not 64/128, heads not divisible, group>16  */
+  OPPO_ERR_CAPACITY = -3,    /* a chunk does not fit its sequence's cache slab      */
+  OPPO_ERR_WORKSPACE = -4,   /* workspace given but smaller than required           */
+  OPPO_ERR_HIP = -5          /* a HIP runtime call failed                           */
+} oppo_status;
+
+/* One attention layer of the scoring model. */
+typedef struct {
+  int32_t num_q_heads;   /* Hq                                            */
+  int32_t num_kv_heads;  /* Hkv, divides Hq; Hq/Hkv <= 16                  */
+  int32_t head_dim;      /* D, 64 or 128                                   */
+  float softmax_scale;   /* s >= 0, finite; the configs use 1/sqrt(D)      */
+} oppo_attn_desc;
+
+/*
+ * Per-sequence KV state that persists across chunks (Sec. 3.1) and, for
+ * sequences deferred by inter-step overlap, across training iterations
+ * (Sec. 3.2; Alg. 1, Buffer.remove keeps unfinished sequences).
+ * Sequence i owns token slots [slot_begin[i], slot_begin[i+1]); its token m
+ * lives in slot slot_begin[i] + m for m < kv_len[i].  The caller owns
+ * everything; a snapshot of the state is a copy of the slabs plus kv_len.
+ */
+typedef struct {
+  void* k;                   /* device bf16 [total_slots][Hkv][D]                       */
+  void* v;                   /* device bf16 [total_slots][Hkv][D]                       */
+  const int64_t* slot_begin; /* host [batch+1], non-decreasing, slot_begin[0] >= 0      */
+  int32_t* kv_len;           /* host [batch]; tokens valid in each slab; oppo_kv_append
+                                advances it on success                                  */
+  int32_t batch;             /* number of sequences (B, or B+Delta slots)               */
+} oppo_kv_cache;
+
+/*
+ * Ragged descriptor of pass t of the streaming loop (Alg. 1, generation loop;
+ * Sec. 3.1): with prompt lengths P_i, final response lengths R_i and chunk size
+ * C, sequence i contributes q_len[i] = min(C, max(0, R_i - t*C)) new rows on top
+ * of kv_before[i] = P_i + min(R_i, t*C) cached tokens; cu_q is the exclusive
+ * prefix sum of q_len (cu_q[0] = 0).  All arrays are host memory; kv_before may
+ * be NULL.  Pure host arithmetic, no GPU needed.
+ * Errors: OPPO_ERR_INVALID for null arrays, B < 0, C < 1, t < 0, negative
+ * lengths or sums that overflow int32.
+ */
+int oppo_chunk_schedule(int32_t B, const int32_t* prompt_len, const int32_t* resp_len,
+                        int32_t C, int32_t t, int32_t* kv_before /* [B] or NULL */,
+                        int32_t* q_len /* [B] */, int32_t* cu_q /* [B+1] */);
+
+/*
+ * Append one chunk per sequence to the cache (step 1 above; byte semantics).
+ * For every i and j < q_len_i = cu_q[i+1]-cu_q[i], row cu_q[i]+j of k_new/v_new
+ * (device bf16 [cu_q[B]][Hkv][D]) is copied bit for bit to slot
+ * slot_begin[i] + kv_len[i] + j of cache->k / cache->v; no other byte of the
+ * cache changes.  On success kv_len[i] += q_len_i (host side, immediately).
+ * q_len_i = 0 is legal (finished or deferred sequence) and costs nothing.
+ * Errors: INVALID (nulls, batch < 0, cu_q not non-decreasing from 0, bad
+ * slot_begin/kv_len), UNSUPPORTED (desc), CAPACITY if any kv_len[i]+q_len_i
+ * exceeds the slab - then nothing is enqueued and kv_len is unchanged.
+ */
+int oppo_kv_append(const oppo_attn_desc* desc, oppo_kv_cache* cache,
+                   const int32_t* cu_q /* host [batch+1] */,
+                   const void* k_new, const void* v_new, void* stream);
+
+/*
+ * Chunked-prefill attention (step 2 above).  cache->kv_len is the length AFTER
+ * the chunk was appended.  Row j of sequence i (row cu_q[i]+j of q and out,
+ * device bf16 [cu_q[B]][Hq][D]) is the token at absolute position
+ * n = kv_len[i] - q_len_i + j and receives
+ *     out = softmax_m( s * <q, K_i[m]> ) . V_i[m]   over keys m = 0..n
+ * (causal mask aligned to the end of the cache).  Scores and both contractions
+ * accumulate in fp32 from bf16 inputs; out is rounded once to bf16
+ * (nearest-even).  A prompt is prefilled by the same call with q_len_i = P_i on
+ * an empty cache.
+ * workspace: device scratch for splitting long key ranges across workgroups
+ * (partial results merged by a second kernel).  NULL / 0 bytes disables
+ * splitting; otherwise it must hold at least
+ * oppo_workspace_bytes(desc, batch, cu_q[batch]) bytes, 256-byte aligned.
+ * Errors: INVALID (nulls, bad cu_q, q_len_i > kv_len[i], kv_len[i] beyond the
+ * slab), UNSUPPORTED, WORKSPACE, HIP.
+ */
+int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cache,
+                            const int32_t* cu_q /* host [batch+1] */,
+                            const void* q, void* out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One-shot causal prefill of whole sequences, without a cache: the reference
+ * side of the streaming-equivalence invariant (Sec. 3.1, Eq. 3) on the device.
+ * Sequence i owns rows [cu_seq[i], cu_seq[i+1]) of q/out (device bf16
+ * [cu_seq[B]][Hq][D]) and of k/v (device bf16 [cu_seq[B]][Hkv][D]); row n of a
+ * sequence sees its keys 0..n.  Same arithmetic and workspace rules as
+ * oppo_chunk_prefill_attn.
+ */
+int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B,
+                          const int32_t* cu_seq /* host [B+1] */,
+                          const void* q, const void* k, const void* v, void* out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bytes of workspace that let the attention entry points split key ranges for
+ * any call with at most max_batch sequences and max_q_tokens query rows in
+ * total.  Returns 0 for an unsupported desc or negative sizes.
+ */
+size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32_t max_q_tokens);
+
+/*
+ * Tuning knobs, process-wide, read at call time (not thread-safe against
+ * concurrent calls).  They change how work is cut and ordered, never what is
+ * computed; tests use them to show that results do not depend on the cut.
+ *   OPPO_OPT_SPLIT_KV : 0 = automatic (default), 1 = never split, n >= 2 =
+ *                       cut every key range into up to n pieces when a
+ *                       workspace is given.
+ *   OPPO_OPT_ORDER    : 0 = longest work first (default), 1 = input order,
+ *                       2 = shortest first.
+ *   OPPO_OPT_NUM_CUS  : compute units the planner balances for (default 256).
+ * Returns OPPO_ERR_INVALID for an unknown option or a negative value.
+ */
+typedef enum { OPPO_OPT_SPLIT_KV = 0, OPPO_OPT_ORDER = 1, OPPO_OPT_NUM_CUS = 2 } oppo_option;
+int oppo_set_option(int option, int value);
+
+/*
+ * Diagnostic: the work list oppo_chunk_prefill_attn would build for a pass whose
+ * sequences have kv_before[i] cached tokens and q_len[i] new rows (host arrays
+ * [B]), given workspace_bytes of workspace.  Nothing is enqueued; no GPU needed.
+ * items receives 8 int32 per workgroup item, in launch order:
+ *   {sequence index, first q row, tokens in tile, position of first token,
+ *    first key, one past last key, partial slot or -1, 0}
+ * n_items receives the count; OPPO_ERR_INVALID if it exceeds max_items.
+ * Each item is replicated over the kv-heads at launch.
+ */
+int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_before, const int32_t* q_len,
+                    size_t workspace_bytes, int32_t* items /* [max_items][8] */, int32_t max_items,
+                    int32_t* n_items);
+
+/* Reason of the last failing call on this thread ("" if none). */
+const char* oppo_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int oppo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPPO_ATTN_H */

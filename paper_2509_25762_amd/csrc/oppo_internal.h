@@ -1,0 +1,69 @@
+// Internal types shared by the host planner and the gfx950 kernels.
+// Not part of the public ABI (see include/oppo_attn.h for that).
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace oppo {
+
+// Rows of the packed (token x q-head-of-group) query tile one workgroup owns:
+// 4 waves x 64 query columns.
+constexpr int kTileRows = 256;
+// Keys per iteration of the key loop.
+constexpr int kKeyTile = 64;
+// Work descriptors travel by value in the kernel-argument segment, so the
+// host arrays are snapshotted at launch time without any staging copy.
+constexpr int kMaxAttnItems = 120;     // 120 * 32 B + header < 4 KiB
+constexpr int kMaxCombineItems = 240;  // 240 * 16 B + header < 4 KiB
+constexpr int kMaxAppendItems = 240;   // 240 * 16 B + header < 4 KiB
+
+// One workgroup's share of the attention: a tile of up to TM tokens of one
+// sequence (all G q-heads of one kv-head; the kv-head comes from the block
+// index) against the key range [k_begin, k_end) of that sequence.
+struct AttnItem {
+  int64_t kv_row0;  // row of the sequence's token 0 in the k/v arrays
+  int32_t q_row0;   // row of the tile's first token in q/out
+  int32_t n_tok;    // tokens in the tile, 1..TM
+  int32_t pos0;     // absolute position of the tile's first token
+  int32_t k_begin;  // first key of the range (multiple of kKeyTile)
+  int32_t k_end;    // one past the last key, <= pos0 + n_tok
+  int32_t part;     // -1: write final bf16 rows; >= 0: partial slot to fill
+};
+static_assert(sizeof(AttnItem) == 32, "AttnItem layout");
+
+// Merge of the partial results of one split tile.
+struct CombineItem {
+  int32_t q_row0;
+  int32_t n_tok;
+  int32_t part0;   // first partial slot; the pieces are consecutive
+  int32_t nsplit;
+};
+
+// One contiguous run of chunk rows going into a cache slab.
+struct AppendItem {
+  int64_t dst_row;  // first slot (token row) in the cache
+  int32_t src_row;  // first row in k_new / v_new
+  int32_t n_tok;
+};
+
+struct LayerShape {
+  int32_t Hq, Hkv, G, D;
+  int32_t TM;       // tokens per query tile = kTileRows / G
+  float c;          // softmax_scale * log2(e)
+};
+
+// Launchers (kernels.hip).  Return a hipError_t as int (0 = success).
+int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
+                     float* part_o, float* part_ml, const AttnItem* items, int n_items, void* stream);
+int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,
+                   const CombineItem* items, int n_items, void* stream);
+int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
+                  const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
+const char* hip_error_string(int err);
+
+// Bytes of one partial slot (all kv-heads): kTileRows rows x (D + 2) floats each.
+inline size_t part_slot_bytes(int Hkv, int D) {
+  return (size_t)Hkv * kTileRows * (size_t)(D + 2) * sizeof(float);
+}
+
+}  // namespace oppo
