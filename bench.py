@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the streamed chunked-prefill path on one MI355X.
+
+One "step" is one streamed episode of the workload: every pass t = 0..T-1 of
+the streaming loop (Alg. 1, generation loop; Sec. 3.1), each pass being
+oppo_kv_append followed by oppo_chunk_prefill_attn over the ragged set of
+unfinished sequences.  Prompts are prefilled once before the timed region
+(reported separately).  Inputs are synthetic and resident in HBM.
+
+Prints ONE JSON line (see README for the field meanings).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def cpu_baseline(cfg, ep, budget_s: float = 12.0):
+    """Times the float64 oracle, as it stands, on a bounded sample: whole
+    sequences of the workload (one-shot causal attention over prompt+response,
+    all heads; only the response rows' share of the FLOPs is credited), taken
+    in order of closeness to the median length until the time budget is spent."""
+    from oracle import bf16_bits_to_f64, causal_attention
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    n = ep.prompt_len.astype(np.int64) + ep.resp_len
+    order = np.argsort(np.abs(n - np.median(n)), kind="stable")
+    flops = 0.0
+    used = []
+    t0 = time.perf_counter()
+    for i in order:
+        lo = int(ep.tok_begin[i])
+        P, R = int(ep.prompt_len[i]), int(ep.resp_len[i])
+        q = bf16_bits_to_f64(ep.q[lo + P:lo + P + R])
+        k = bf16_bits_to_f64(ep.k[lo:lo + P + R])
+        v = bf16_bits_to_f64(ep.v[lo:lo + P + R])
+        causal_attention(q, k, v, P + np.arange(R), cfg.softmax_scale)
+        flops += 4.0 * cfg.head_dim * cfg.num_q_heads * (R * P + R * (R + 1) / 2.0)
+        used.append(int(i))
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{len(used)} of {cfg.batch} sequences nearest the median length, response rows x all heads, "
+                  f"float64 numpy, {dt:.1f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload index 1..5 (default: the Llama-3-8B-shape layer)")
+    ap.add_argument("--copies", type=int, default=4, help="independent cache copies rotated between episodes")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-workspace", action="store_true", help="disable split-KV")
+    ap.add_argument("--details", type=str, default="", help="write per-pass details to this JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2509_25762_amd import binding as ob
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import CONFIGS, build_episode, episode_work
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ob.load()
+    cfg = CONFIGS[args.config]
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
+    T = len(chunks) - 1
+    copies = [StreamedEpisode(ep, chunks, use_workspace=not args.no_workspace) for _ in range(max(1, args.copies))]
+    # shared inputs are identical across copies; only the cache slabs and outputs differ
+    work = episode_work(cfg, [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
+    flops = sum(w["flops"] for w in work)
+    kv_bytes = sum(w["kv_read_bytes"] for w in work)
+    tot_bytes = sum(w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"] for w in work)
+
+    # prompt prefill, once per copy, timed on its own
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for se in copies:
+        se.reset(0)
+        se.run_step(0)
+    torch.cuda.synchronize()
+    prompt_ms = (time.perf_counter() - t0) * 1e3 / len(copies)
+
+    def episode(se):
+        se.reset(1)
+        for t in range(1, T + 1):
+            se.run_step(t)
+
+    for w in range(args.warmup):
+        episode(copies[w % len(copies)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        episode(copies[s % len(copies)])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+
+    # attention kernel alone: HIP events on the launch stream around every attention call
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(T)]
+          for _ in range(args.steps)]
+    evap = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(T)]
+            for _ in range(args.steps)]
+    for s in range(args.steps):
+        se = copies[s % len(copies)]
+        se.reset(1)
+        for t in range(1, T + 1):
+            st = se.steps[t]
+            evap[s][t - 1][0].record()
+            ob.oppo_kv_append(se.desc, se.cache, st.cu_q, st.k, st.v)
+            evap[s][t - 1][1].record()
+            ev[s][t - 1][0].record()
+            ob.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, st.q, st.out, se.workspace)
+            ev[s][t - 1][1].record()
+    torch.cuda.synchronize()
+    attn_ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev])      # [steps, T]
+    app_ms = np.array([[a.elapsed_time(b) for a, b in row] for row in evap])
+    attn_pass_ms = attn_ms.mean(axis=0)
+    attn_total_ms = float(attn_pass_ms.sum())
+    achieved = flops / (attn_total_ms * 1e-3) / 1e12
+
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    t_roof_ms = sum(max(w["flops"] / (PEAK_BF16_TFLOPS * 1e12),
+                        (w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"]) / (PEAK_HBM_GBPS * 1e9)) for w in work) * 1e3
+    line = {
+        "metric": "chunked-prefill attn TFLOP/s + KV GB/s, % of MI355X roofline, 1 GPU",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): B={cfg.batch}, Hq/Hkv/D={cfg.num_q_heads}/"
+                               f"{cfg.num_kv_heads}/{cfg.head_dim}, C={cfg.chunk}, {T} passes per episode, "
+                               f"{int(sum(w['rows'] for w in work))} response rows",
+                   "step": "one streamed episode (kv_append + chunk_prefill_attn per pass)",
+                   "cache_copies_rotated": len(copies)},
+        "kv_read_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
+        "total_GBps": tot_bytes / (ms_per_step * 1e-3) / 1e9,
+        "frac_of_roofline_episode": t_roof_ms / ms_per_step,
+        "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "frac_hbm_peak": tot_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "prompt_prefill_ms": prompt_ms,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "attn_fwd_kernel (+ split-KV merge where used)",
+                     "launches_per_step": T, "avg_launch_ms": attn_total_ms / T,
+                     "first_pass": {"ms": float(attn_pass_ms[0]),
+                                    "tflops": work[0]["flops"] / (attn_pass_ms[0] * 1e-3) / 1e12}},
+        "append_ms_per_step": float(app_ms.mean(axis=0).sum()),
+    }
+    if args.details:
+        det = {"attn_pass_ms": attn_pass_ms.tolist(), "append_pass_ms": app_ms.mean(axis=0).tolist(),
+               "work": work, "ms_per_step": ms_per_step}
+        with open(args.details, "w") as f:
+            json.dump(det, f, indent=1)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, ep)
+    else:
+        line["cpu_baseline"] = None
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
