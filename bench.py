@@ -71,6 +71,7 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies rotated between episodes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-workspace", action="store_true", help="disable split-KV")
+    ap.add_argument("--split", type=int, default=0, help="split-KV policy (0 auto, 1 off, n forced)")
     ap.add_argument("--details", type=str, default="", help="write per-pass details to this JSON file")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -86,6 +87,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     ob.load()
+    if args.split:
+        ob.oppo_set_option(ob.OPT_SPLIT_KV, args.split)
     cfg = CONFIGS[args.config]
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)

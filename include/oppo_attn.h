@@ -158,7 +158,11 @@ size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32
  *   OPPO_OPT_NUM_CUS  : compute units the planner balances for (default 256).
  * Returns OPPO_ERR_INVALID for an unknown option or a negative value.
  */
-typedef enum { OPPO_OPT_SPLIT_KV = 0, OPPO_OPT_ORDER = 1, OPPO_OPT_NUM_CUS = 2 } oppo_option;
+typedef enum {
+  OPPO_OPT_SPLIT_KV = 0,
+  OPPO_OPT_ORDER = 1,
+  OPPO_OPT_NUM_CUS = 2
+} oppo_option;
 int oppo_set_option(int option, int value);
 
 /*

@@ -13,9 +13,9 @@ constexpr int kTileRows = 256;
 constexpr int kKeyTile = 64;
 // Work descriptors travel by value in the kernel-argument segment, so the
 // host arrays are snapshotted at launch time without any staging copy.
-constexpr int kMaxAttnItems = 120;     // 120 * 32 B + header < 4 KiB
-constexpr int kMaxCombineItems = 240;  // 240 * 16 B + header < 4 KiB
-constexpr int kMaxAppendItems = 240;   // 240 * 16 B + header < 4 KiB
+constexpr int kMaxAttnItems = 1000;     // 1000 * 32 B + header < 32 KiB
+constexpr int kMaxCombineItems = 1000;  // 1000 * 16 B + header
+constexpr int kMaxAppendItems = 1000;   // 1000 * 16 B + header
 
 // One workgroup's share of the attention: a tile of up to TM tokens of one
 // sequence (all G q-heads of one kv-head; the kv-head comes from the block
