@@ -109,9 +109,9 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 //   * operand fragments are read from LDS several steps before the MFMA that
 //     consumes them (rolling register buffers ka / vf), the first K fragments of
 //     the next tile already during the current tile's second product;
-//   * the exp2 / convert / row-sum work of one 16-key group is issued between
-//     the MFMAs of the previous group, about six vector ALU instructions per
-//     32-cycle MFMA.
+//   * the two MFMA chains (S^T, then O^T) are kept dense; the softmax in between
+//     is pure vector ALU work that the other wave of the SIMD overlaps with its
+//     own MFMAs.
 // K/V tiles go straight from global memory into a ring of four LDS stages, three
 // tiles ahead: the loads of tile t+3 are issued after barrier t into the stage
 // last read before that barrier, and each wave waits for its own loads of tile
@@ -132,7 +132,6 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int KDEPTH = 3;          // k-steps of K fragments kept in flight
   constexpr int VDEPTH = 4;          // V^T fragments kept in flight
   constexpr int PV_STEPS = 4 * DB;   // MFMAs of the second product per tile
-  constexpr int PAIRS = 4 / DB;      // probability pairs converted per PV step
   static_assert(IPW >= 1 && NT == 512, "tile smaller than the workgroup");
   static_assert(KK >= KDEPTH && KK >= VDEPTH && PV_STEPS >= VDEPTH, "pipeline deeper than the tile");
 
@@ -284,14 +283,9 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       rs0 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, rs0, false);
   };
 
-  auto tile_step = [&](auto BUFC, int t) __attribute__((always_inline)) {
-    constexpr int buf = decltype(BUFC)::value;
-    constexpr int nbuf = (buf + 1) % NSTAGE;
-    const bool pre = t + 3 < nt;
-    const bool next = t + 1 < nt;
-    if (pre) issue_tile((buf + 3) % NSTAGE, t + 3);
-
-    // ---- S^T = K Q^T; the first V^T fragments are fetched under its last MFMAs ------
+  // S^T = K Q^T of the tile in stage kbuf (its first K fragments are already in ka);
+  // the first V^T fragments are fetched under the last MFMAs
+  auto qk_phase = [&](int kbuf) __attribute__((always_inline)) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -301,12 +295,21 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % KDEPTH][0], qf[kk], s[0], 0, 0, 0);
       s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % KDEPTH][1], qf[kk], s[1], 0, 0, 0);
       if (kk + KDEPTH < KK) {
-        ka[kk % KDEPTH][0] = ldk(buf, kk + KDEPTH, 0);
-        ka[kk % KDEPTH][1] = ldk(buf, kk + KDEPTH, 1);
+        ka[kk % KDEPTH][0] = ldk(kbuf, kk + KDEPTH, 0);
+        ka[kk % KDEPTH][1] = ldk(kbuf, kk + KDEPTH, 1);
       }
-      if (kk >= KK - VDEPTH) vf[kk - (KK - VDEPTH)] = ldv(buf, kk - (KK - VDEPTH));
+      if (kk >= KK - VDEPTH) vf[kk - (KK - VDEPTH)] = ldv(kbuf, kk - (KK - VDEPTH));
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+
+  auto tile_step = [&](auto BUFC, int t) __attribute__((always_inline)) {
+    constexpr int buf = decltype(BUFC)::value;
+    constexpr int nbuf = (buf + 1) % NSTAGE;
+    const bool pre = t + 3 < nt;
+    const bool next = t + 1 < nt;
+    if (pre) issue_tile((buf + 3) % NSTAGE, t + 3);
+    qk_phase(buf);
 
     // ---- causal / range mask on tiles that cross a limit -----------------------
     const int key0 = it.k_begin + t * BN;
@@ -346,18 +349,16 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     rs0 = 0.f;
     rs1 = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) exp_pair(0, j);
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) exp_pair(g, j);
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- O^T += V^T P^T, with the next group's exp2 work between the MFMAs ----------
+    // ---- O^T += V^T P^T -----------------------------------------------------------------
 #pragma unroll
     for (int step = 0; step < PV_STEPS; ++step) {
       const int g = step / DB, db = step % DB;
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step % VDEPTH], pf[g].v, o[db], 0, 0, 0);
-      if (g + 1 < 4) {
-#pragma unroll
-        for (int jj = 0; jj < PAIRS; ++jj) exp_pair(g + 1, db * PAIRS + jj);
-      }
       if (step + VDEPTH < PV_STEPS) vf[step % VDEPTH] = ldv(buf, step + VDEPTH);
       if (step >= PV_STEPS - KDEPTH && next) {
         ka[step - (PV_STEPS - KDEPTH)][0] = ldk(nbuf, step - (PV_STEPS - KDEPTH), 0);

@@ -1,0 +1,211 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header
+declares, validates arguments before touching the GPU, and its host logic
+(chunk schedule, work planner) agrees with the oracle / with first principles.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import chunk_schedule as oracle_schedule
+from paper_2509_25762_amd import binding as ob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ob.LIB_PATH):
+        from paper_2509_25762_amd import build
+        build.build(verbose=False)
+    return ob.load()
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "oppo_attn.h")).read()
+    declared = set(re.findall(r"\b(oppo_[a-z_]+)\s*\(", header))
+    assert declared == set(ob.EXPORTS), declared ^ set(ob.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} not exported"
+    assert ob.oppo_version() >= 100
+
+
+def test_schedule_matches_oracle(lib):
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        B = int(rng.integers(0, 40))
+        P = rng.integers(0, 3000, size=B)
+        R = rng.integers(0, 5000, size=B)
+        C = int(rng.integers(1, 1200))
+        t = int(rng.integers(0, 12))
+        kvb, ql, cu = ob.oppo_chunk_schedule(P, R, C, t)
+        okvb, oql, ocu = oracle_schedule(P, R, C, t)
+        assert np.array_equal(kvb, okvb) and np.array_equal(ql, oql) and np.array_equal(cu, ocu)
+
+
+def test_schedule_rejects_bad_arguments(lib):
+    for args in ([[1], [1], 0, 0], [[1], [1], 4, -1], [[-1], [1], 4, 0], [[1], [-2], 4, 0]):
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_chunk_schedule(*args)
+        assert e.value.code == ob.OPPO_ERR_INVALID
+    with pytest.raises(ob.OppoError):
+        ob.oppo_chunk_schedule([2 ** 31 - 5], [100], 4, 0)          # P + R overflows int32
+    assert ob.oppo_last_error() != ""
+
+
+def _desc(Hq=32, Hkv=8, D=128, s=0.0884):
+    return ob.make_desc(Hq, Hkv, D, s)
+
+
+def _fake_cache(slot_begin, kv_len):
+    """A cache whose device pointers are never dereferenced (validation fails first)."""
+    return ob.KVCache(0x1000, 0x2000, np.asarray(slot_begin), np.asarray(kv_len))
+
+
+def test_descriptor_validation(lib):
+    cache = _fake_cache([0, 10], [0])
+    for desc, code in [(_desc(D=96), ob.OPPO_ERR_UNSUPPORTED), (_desc(Hq=30), ob.OPPO_ERR_UNSUPPORTED),
+                       (_desc(Hq=64, Hkv=2), ob.OPPO_ERR_UNSUPPORTED), (_desc(s=0.0), ob.OPPO_ERR_INVALID),
+                       (_desc(s=float("nan")), ob.OPPO_ERR_INVALID), (_desc(Hq=0), ob.OPPO_ERR_INVALID)]:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_kv_append(desc, cache, [0, 1], 0x3000, 0x4000, stream=0)
+        assert e.value.code == code
+        assert ob.oppo_workspace_bytes(desc, 4, 100) == 0
+    assert ob.oppo_workspace_bytes(_desc(), 4, 100) > 0
+    assert ob.oppo_workspace_bytes(_desc(), -1, 100) == 0
+
+
+def test_append_validation_leaves_lengths_untouched(lib):
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 0])
+    cases = [([0, 3, 6], ob.OPPO_ERR_CAPACITY),      # 6 + 3 > 8
+             ([1, 3, 6], ob.OPPO_ERR_INVALID),       # cu_q[0] != 0
+             ([0, 3, 2], ob.OPPO_ERR_INVALID)]       # decreasing
+    for cu, code in cases:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_kv_append(desc, cache, cu, 0x3000, 0x4000, stream=0)
+        assert e.value.code == code
+        assert cache.kv_len.tolist() == [6, 0]
+    bad = _fake_cache([0, 8, 20], [9, 0])            # kv_len beyond the slab
+    with pytest.raises(ob.OppoError) as e:
+        ob.oppo_kv_append(desc, bad, [0, 0, 0], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID
+    dec = _fake_cache([0, 8, 4], [0, 0])             # slot_begin decreases
+    with pytest.raises(ob.OppoError) as e:
+        ob.oppo_kv_append(desc, dec, [0, 0, 0], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID
+    # a pass in which nobody has rows is legal and needs no device at all
+    ob.oppo_kv_append(desc, cache, [0, 0, 0], None, None, stream=0)
+    assert cache.kv_len.tolist() == [6, 0]
+
+
+def test_attention_validation(lib):
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 2])
+    with pytest.raises(ob.OppoError) as e:            # 3 query rows, only 2 cached tokens
+        ob.oppo_chunk_prefill_attn(desc, cache, [0, 1, 4], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID
+
+    class FakeWs:                                      # unaligned / too small workspaces
+        def __init__(self, ptr, n):
+            self.ptr, self.n = ptr, n
+
+        def is_contiguous(self):
+            return True
+
+        def data_ptr(self):
+            return self.ptr
+
+        def numel(self):
+            return self.n
+
+        def element_size(self):
+            return 1
+
+    for ws in (FakeWs(0x10001, 1 << 30), FakeWs(0x10000, 4096)):
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_chunk_prefill_attn(desc, cache, [0, 1, 2], 0x3000, 0x4000, ws, stream=0)
+        assert e.value.code == ob.OPPO_ERR_WORKSPACE
+    # nothing to do: legal without any device pointer
+    ob.oppo_chunk_prefill_attn(desc, cache, [0, 0, 0], None, None, stream=0)
+    ob.oppo_full_prefill_ref(desc, [0, 0, 0], None, None, None, None, stream=0)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_full_prefill_ref(desc, [0, 5, 3], 0x1, 0x2, 0x3, 0x4, stream=0)
+
+
+def test_options_validation(lib):
+    with pytest.raises(ob.OppoError):
+        ob.oppo_set_option(99, 1)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_set_option(ob.OPT_ORDER, 7)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_set_option(ob.OPT_SPLIT_KV, -1)
+    ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)
+    ob.oppo_set_option(ob.OPT_ORDER, 0)
+
+
+def _check_plan(desc, kv_before, q_len, items, TM):
+    """Every (sequence, query tile) has its key range [0, keys) covered exactly
+    once by pieces on 64-key boundaries; pieces of a split tile own distinct
+    partial slots; whole tiles write final output."""
+    by_tile = {}
+    for seq, q_row0, n_tok, pos0, k0, k1, part, _ in items.tolist():
+        by_tile.setdefault((seq, q_row0), []).append((k0, k1, part, n_tok, pos0))
+    want = set()
+    row = 0
+    for i, (kvb, ql) in enumerate(zip(kv_before, q_len)):
+        for j0 in range(0, ql, TM):
+            want.add((i, row + j0))
+        row += ql
+    assert set(by_tile) == want
+    parts = []
+    row_of = np.concatenate([[0], np.cumsum(q_len)])
+    for (seq, q_row0), pieces in by_tile.items():
+        pieces.sort()
+        n_tok, pos0 = pieces[0][3], pieces[0][4]
+        j0 = q_row0 - row_of[seq]
+        assert pos0 == kv_before[seq] + j0 and n_tok == min(TM, q_len[seq] - j0)
+        assert pieces[0][0] == 0 and pieces[-1][1] == pos0 + n_tok
+        for (a0, a1, _, _, _), (b0, _, _, _, _) in zip(pieces, pieces[1:]):
+            assert a1 == b0 and a1 % 64 == 0
+        if len(pieces) == 1:
+            assert pieces[0][2] == -1
+        else:
+            parts += [p[2] for p in pieces]
+            assert all(p[2] >= 0 for p in pieces)
+    assert len(parts) == len(set(parts))
+    return len(parts)
+
+
+def test_planner_covers_every_key_exactly_once(lib):
+    desc = _desc()
+    ws = ob.oppo_workspace_bytes(desc, 64, 1 << 16)
+    rng = np.random.default_rng(3)
+    for trial in range(30):
+        B = int(rng.integers(1, 70))
+        kvb = rng.integers(0, 6000, size=B)
+        ql = np.where(rng.random(B) < 0.3, 0, rng.integers(1, 300, size=B))
+        for split in (0, 1, 2, 5):
+            ob.oppo_set_option(ob.OPT_SPLIT_KV, split)
+            items = ob.oppo_plan_debug(desc, kvb, ql, ws)
+            n_parts = _check_plan(desc, kvb, ql, items, 256 // 4)
+            if split == 1:
+                assert n_parts == 0
+            # default order: longest key range first
+            lens = items[:, 5] - items[:, 4]
+            assert np.all(np.diff(lens) <= 0)
+    ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)
+    # without a workspace nothing is ever split
+    items = ob.oppo_plan_debug(desc, [5000], [256], 0)
+    assert np.all(items[:, 6] == -1) and len(items) == 4
+
+
+def test_planner_splits_a_thin_tail_but_not_a_full_batch(lib):
+    desc = _desc()
+    ws = ob.oppo_workspace_bytes(desc, 64, 1 << 16)
+    tail = ob.oppo_plan_debug(desc, [3000], [256], ws)             # one straggler: 32 workgroups unsplit
+    assert len(tail) > 4 and np.all(tail[:, 6] >= 0)
+    full = ob.oppo_plan_debug(desc, np.full(64, 700), np.full(64, 256), ws)   # 2048 workgroups
+    assert np.all(full[:, 6] == -1) and len(full) == 256

@@ -1,0 +1,143 @@
+"""GPU parity at the full sizes of the five synthetic workloads, in the launch
+configuration bench.py times (uniform chunks of C, automatic split-KV, workspace).
+
+A full float64 pass over 0.7-12 TFLOP is out of reach for the oracle, so the
+large workloads are checked on rows the oracle computes one by one:
+  * every row of the shortest sequence, for the q-heads of the first and the
+    last kv-head;
+  * first and last row of every chunk of every sequence, one q-head each;
+  * the chunk-boundary rows plus random rows of the longest sequence, for the
+    q-heads of the first and the last kv-head;
+  * random (sequence, q-head, position) triples over all rows;
+and on properties that hold at any size: the streamed outputs agree with the
+device's one-shot prefill on ALL rows, and the final cache equals the inputs bit
+for bit with every spare slot still holding its sentinel.
+"""
+import numpy as np
+import pytest
+
+from oracle import bf16_bits_to_f64, causal_attention, chunk_schedule, num_steps
+from paper_2509_25762_amd.workload import CONFIGS, build_episode
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-2
+MEAN_ABS = 2e-3
+N_RANDOM = 4096
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_25762_amd import binding, episode
+    binding.load()
+    return binding, episode, torch
+
+
+def oracle_chunks(P, R, C):
+    steps = [[int(p) for p in P]]
+    for t in range(num_steps(R, C)):
+        steps.append([int(x) for x in chunk_schedule(P, R, C, t)[1]])
+    return steps
+
+
+class RowOracle:
+    """Oracle rows of one sequence, K/V widened once."""
+
+    def __init__(self, ep, i):
+        self.ep, self.i = ep, i
+        self.lo, self.hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        self.k = bf16_bits_to_f64(ep.k[self.lo:self.hi])
+        self.v = bf16_bits_to_f64(ep.v[self.lo:self.hi])
+
+    def rows(self, positions, heads):
+        """float64 [len(positions), len(heads), D] for the given q-heads."""
+        cfg = self.ep.cfg
+        pos = np.asarray(positions, dtype=np.int64)
+        out = np.empty((len(pos), len(heads), cfg.head_dim))
+        for a, h in enumerate(heads):
+            g = h // cfg.group
+            q = bf16_bits_to_f64(self.ep.q[self.lo + pos, h])[:, None, :]
+            out[:, a] = causal_attention(q, self.k[:, g:g + 1], self.v[:, g:g + 1], pos, cfg.softmax_scale)[:, 0]
+        return out
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_full_size_config(gpu, idx):
+    binding, episode, torch = gpu
+    cfg = CONFIGS[idx]
+    ep = build_episode(cfg, threads=16)
+    P, R = ep.prompt_len, ep.resp_len
+    B, Hq, G = cfg.batch, cfg.num_q_heads, cfg.group
+    chunks = oracle_chunks(P, R, cfg.chunk)
+    print(f"config {idx}: {int(ep.tok_begin[-1])} tokens, {len(chunks) - 1} response passes", flush=True)
+    se = episode.StreamedEpisode(ep, chunks)
+    se.run()
+    torch.cuda.synchronize()
+    out_dev = se.scatter_outputs()
+    out = out_dev.cpu().numpy().view(np.uint16)
+    assert np.isfinite(bf16_bits_to_f64(out[:: max(1, out.shape[0] // 4096)])).all()
+
+    # ---- cache: bit-exact, spare slots untouched (compared on the device) ----------
+    for i in range(B):
+        lo, hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        b, e = int(se.slot_begin[i]), int(se.slot_begin[i + 1])
+        n = hi - lo
+        assert se.cache.kv_len[i] == n
+        assert torch.equal(se.cache_k[b:b + n], se.k_all[lo:hi]), f"K cache of sequence {i}"
+        assert torch.equal(se.cache_v[b:b + n], se.v_all[lo:hi]), f"V cache of sequence {i}"
+        assert bool((se.cache_k[b + n:e] == -1).all()) and bool((se.cache_v[b + n:e] == -1).all())
+
+    # ---- streamed == one-shot prefill on the device, all rows ----------------------
+    full = se.full_prefill()
+    torch.cuda.synchronize()
+    diff = (out_dev.view(torch.bfloat16).float() - full.view(torch.bfloat16).float()).abs()
+    assert float(diff.max()) <= MAX_ABS, f"chunked vs one-shot max {float(diff.max()):.3e}"
+    assert float(diff.mean()) <= MEAN_ABS
+    same = float((out_dev == full).float().mean())
+    print(f"config {idx}: chunked vs one-shot max {float(diff.max()):.3e} mean {float(diff.mean()):.3e} "
+          f"bit-identical {same * 100:.1f}%", flush=True)
+    del full, diff
+
+    # ---- sampled rows against the oracle ------------------------------------------
+    errs = []
+
+    def check(i, positions, heads, orc=None):
+        orc = orc or RowOracle(ep, i)
+        positions = np.asarray(positions, dtype=np.int64)
+        ref = orc.rows(positions, heads)
+        got = bf16_bits_to_f64(out[orc.lo + positions][:, heads])
+        errs.append(np.abs(got - ref).ravel())
+        return orc
+
+    n_tok = P.astype(np.int64) + R
+    edge_heads = list(range(0, G)) + list(range(Hq - G, Hq))       # first and last kv-head
+    shortest, longest = int(np.argmin(n_tok)), int(np.argmax(n_tok))
+    check(shortest, np.arange(n_tok[shortest]), edge_heads)
+    rng = np.random.default_rng(cfg.seed + 1)
+    for i in range(B):
+        bounds = [0, int(P[i]) - 1]
+        for t in range(num_steps(R, cfg.chunk)):
+            kvb, ql, _ = chunk_schedule(P[i:i + 1], R[i:i + 1], cfg.chunk, t)
+            if ql[0] > 0:
+                bounds += [int(kvb[0]), int(kvb[0] + ql[0] - 1)]
+        orc = check(i, sorted(set(bounds)), [i % Hq])
+        if i == longest:
+            extra = rng.integers(0, n_tok[i], size=64)
+            check(i, sorted(set(bounds) | set(int(x) for x in extra)), edge_heads, orc)
+    seqs = rng.integers(0, B, size=N_RANDOM)
+    for i in np.unique(seqs):
+        cnt = int(np.sum(seqs == i))
+        pos = rng.integers(0, n_tok[i], size=cnt)
+        heads = rng.integers(0, Hq, size=cnt)
+        orc = RowOracle(ep, int(i))
+        for h in np.unique(heads):
+            check(int(i), pos[heads == h], [int(h)], orc)
+    err = np.concatenate(errs)
+    print(f"config {idx}: {err.size} sampled output elements, max abs {err.max():.3e}, mean abs {err.mean():.3e}",
+          flush=True)
+    assert err.max() <= MAX_ABS
+    assert err.mean() <= MEAN_ABS
