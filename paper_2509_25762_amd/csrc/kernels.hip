@@ -67,6 +67,10 @@ static_assert(sizeof(AppendParams) <= 32768, "kernel arguments are kept within 3
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+__device__ __forceinline__ s16x4 lds_read_tr16_l(const __attribute__((address_space(3))) unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+}
+
 // Exchange of the two 32-lane halves of a wave: every lane receives the value
 // held by the lane 32 away (v_permlane32_swap; the compiler's builtin for it
 // mis-assigns the second result, so the instruction is written out).
@@ -103,19 +107,15 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 }
 
 // Eight waves, each owning 32 query columns of the 256-row tile; two waves share
-// a SIMD, so one wave's MFMAs fill the matrix pipe while the other waits for an
-// operand or runs vector ALU work.  Within a wave the instruction stream is laid
-// out by hand (fenced with sched_barrier so the compiler keeps it):
-//   * operand fragments are read from LDS several steps before the MFMA that
-//     consumes them (rolling register buffers ka / vf), the first K fragments of
-//     the next tile already during the current tile's second product;
-//   * the two MFMA chains (S^T, then O^T) are kept dense; the softmax in between
-//     is pure vector ALU work that the other wave of the SIMD overlaps with its
-//     own MFMAs.
-// K/V tiles go straight from global memory into a ring of four LDS stages, three
-// tiles ahead: the loads of tile t+3 are issued after barrier t into the stage
-// last read before that barrier, and each wave waits for its own loads of tile
-// t+2 before barrier t+1, after which that tile may be read.
+// a SIMD.  On this hardware vector ALU instructions hide under MFMAs only when
+// the two are mixed finely (a handful of vector instructions per MFMA), so the
+// instruction stream is laid out by hand and fenced with sched_barrier: see the
+// main loop.  Operand fragments are read from LDS several steps before the MFMA
+// that consumes them (rolling register buffers ka / vf).
+// K/V tiles go straight from global memory into a ring of four LDS stages, two
+// tiles ahead: the loads of tile t+2 are issued after the barrier that opens
+// iteration t, into the stage whose last reader finished before that barrier,
+// and each wave waits for its own loads before the barrier that closes it.
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = 512;            // threads
@@ -129,18 +129,17 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NSTAGE = 4;
   constexpr int RPI = 1024 / ROWB;     // tile rows one wave-wide 16-byte load covers
   constexpr int IPW = BN / RPI / 8;    // such loads per wave, per tile, for K and again for V
-  constexpr int KDEPTH = 3;          // k-steps of K fragments kept in flight
-  constexpr int VDEPTH = 4;          // V^T fragments kept in flight
-  constexpr int PV_STEPS = 4 * DB;   // MFMAs of the second product per tile
+  constexpr int KDEPTH = 4;          // K fragments kept in flight
+  constexpr int VDEPTH = DB;         // V^T fragments kept in flight
   static_assert(IPW >= 1 && NT == 512, "tile smaller than the workgroup");
-  static_assert(KK >= KDEPTH && KK >= VDEPTH && PV_STEPS >= VDEPTH, "pipeline deeper than the tile");
 
-  // one array per stage and operand, so that the compiler can tell a pending
-  // direct-to-LDS load of one stage from the fragment reads of another
-  __shared__ __attribute__((aligned(1024))) unsigned char sk0[TILE_BYTES], sk1[TILE_BYTES], sk2[TILE_BYTES], sk3[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char sv0[TILE_BYTES], sv1[TILE_BYTES], sv2[TILE_BYTES], sv3[TILE_BYTES];
-  auto SK = [&](int b) __attribute__((always_inline)) { return b == 0 ? sk0 : b == 1 ? sk1 : b == 2 ? sk2 : sk3; };
-  auto SV = [&](int b) __attribute__((always_inline)) { return b == 0 ? sv0 : b == 1 ? sv1 : b == 2 ? sv2 : sv3; };
+  // K stages and V stages are two arrays of at most 64 KiB each, so that every
+  // fragment read is "per-lane base register + immediate offset" (the LDS
+  // instructions take 16-bit offsets)
+  __shared__ __attribute__((aligned(1024))) unsigned char sk[NSTAGE][TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sv[NSTAGE][TILE_BYTES];
+  auto SK = [&](int b) __attribute__((always_inline)) { return &sk[b][0]; };
+  auto SV = [&](int b) __attribute__((always_inline)) { return &sv[b][0]; };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -241,17 +240,35 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       voff[db] = vrow * ROWB + ((lg ^ ((vrow & VSWZ_MASK) << 2)) * 16) + (j & 1) * 8;
     }
   }
+  // per-lane base pointers; stage, key half and group then are immediate offsets
+  // (made opaque to the optimiser, which would otherwise fold the array address
+  // into each read and rebuild the sum with a vector instruction every time)
+  typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
+  lds_cptr kptr[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)koff[kk];
+    asm volatile("" : "+v"(a));
+    kptr[kk] = (lds_cptr)(uintptr_t)a;
+  }
+  lds_cptr vptr[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    uint32_t a = lds_addr_of(&sv[0][0]) + (uint32_t)voff[db];
+    asm volatile("" : "+v"(a));
+    vptr[db] = (lds_cptr)(uintptr_t)a;
+  }
   // K fragment (A operand of S^T = K Q^T): keys kb*32 + l32, elements kk*16 + 8*hi..
   auto ldk = [&](int buf, int kk, int kb) __attribute__((always_inline)) -> bf16x8 {
-    return *(const bf16x8*)(SK(buf) + kb * 32 * ROWB + koff[kk]);
+    return *(const __attribute__((address_space(3))) bf16x8*)(kptr[kk] + buf * TILE_BYTES + kb * 32 * ROWB);
   };
   // V^T fragment (A operand of O^T += V^T P^T) of PV step `step` = (16-key group g, d-block db)
   auto ldv = [&](int buf, int step) __attribute__((always_inline)) -> bf16x8 {
     const int g = step / DB, db = step % DB;
-    const unsigned char* vp = SV(buf) + g * 16 * ROWB + voff[db];
+    lds_cptr vp = vptr[db] + buf * TILE_BYTES + g * 16 * ROWB;
     union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
-    cat.h.a = lds_read_tr16(vp);
-    cat.h.b = lds_read_tr16(vp + 8 * ROWB);
+    cat.h.a = lds_read_tr16_l(vp);
+    cat.h.b = lds_read_tr16_l(vp + 8 * ROWB);
     return cat.v;
   };
 
@@ -261,141 +278,199 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   const float tau = 8.0f / c;
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
-  f32x16 s[2];            // S^T of the current tile: keys kb*32.. x this wave's 32 columns
-  bf16x8 ka[KDEPTH][2];   // K fragments in flight
-  bf16x8 vf[VDEPTH];      // V^T fragments in flight
-  union { bf16x2 h[4]; bf16x8 v; } pf[4];  // probabilities of 16-key group g, B operand layout
+  // ------------------------------------------------------------------------------
+  // Main loop, software-pipelined over 32-key units (two per 64-key tile).  The
+  // body of unit u issues, interleaved instruction by instruction,
+  //   * the MFMAs of S^T for unit u+1            (one dependent chain),
+  //   * the MFMAs of O^T += V^T P^T for unit u-1 (DB independent chains),
+  //   * the exp2 / bf16 rounding / row-sum vector work of unit u,
+  // so the matrix pipe always has an independent MFMA to run and the vector ALU
+  // work (about three instructions per MFMA) is spread evenly under it.
+  constexpr int QS = KK;          // S^T MFMAs per unit
+  constexpr int PS = 2 * DB;      // O^T MFMAs per unit
+  constexpr int PPS = 8 / QS;     // probability pairs handled per step
+  static_assert(QS == PS && QS % KDEPTH == 0 && PS % VDEPTH == 0, "pipeline shape");
+
+  f32x16 s[2];                                   // s[u & 1] = S^T of unit u
+  bf16x8 ka[KDEPTH];                             // K fragments in flight: step j of a unit sits in ka[j % KDEPTH]
+  bf16x8 vf[VDEPTH];                             // V^T fragments in flight, likewise
+  union { bf16x2 h[8]; bf16x8 v[2]; } pf[2];     // pf[u & 1] = probabilities of unit u, B-operand layout
   float mc = 0.f, rs0 = 0.f, rs1 = 0.f;
 
-  // probabilities 2j, 2j+1 of group g: exp2, round to bf16, add to the row sum
-  // (the sum uses the rounded values, like the numerator does)
-  auto exp_pair = [&](int g, int j) __attribute__((always_inline)) {
-    const int kb = g >> 1, u = g & 1;
-    const float p0 = fast_exp2(fmaf(s[kb][8 * u + 2 * j], c, -mc));
-    const float p1 = fast_exp2(fmaf(s[kb][8 * u + 2 * j + 1], c, -mc));
+  const int U = (k_hi - it.k_begin + 31) / 32;   // units of this item
+
+  // fragment of unit (stage st, key half kb): K step kk, or V step j = group * DB + d-block
+  auto ldk_u = [&](int st, int kb, int kk) __attribute__((always_inline)) -> bf16x8 { return ldk(st, kk, kb); };
+  auto ldv_u = [&](int st, int kb, int j) __attribute__((always_inline)) -> bf16x8 {
+    return ldv(st, (2 * kb + j / DB) * DB + j % DB);
+  };
+
+  // probabilities 2p, 2p+1 of the unit in s[cur]: exp2, round to bf16, add to the
+  // row sum (the sum uses the rounded values, like the numerator does)
+  auto exp_pair = [&](int cur, int pr) __attribute__((always_inline)) {
+    const float p0 = fast_exp2(fmaf(s[cur][2 * pr], c, -mc));
+    const float p1 = fast_exp2(fmaf(s[cur][2 * pr + 1], c, -mc));
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
-    pf[g].h[j] = pk;
-    if (j & 1)
+    pf[cur].h[pr] = pk;
+    if (pr & 1)
       rs1 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, rs1, false);
     else
       rs0 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, rs0, false);
   };
 
-  // S^T = K Q^T of the tile in stage kbuf (its first K fragments are already in ka);
-  // the first V^T fragments are fetched under the last MFMAs
-  auto qk_phase = [&](int kbuf) __attribute__((always_inline)) {
+  auto unit_body = [&](auto BC, int u) __attribute__((always_inline)) {
+    constexpr int b = decltype(BC)::value;                     // u mod 8
+    constexpr int st_c = b / 2, kb_c = b % 2;                   // unit u
+    constexpr int st_n = ((b + 1) % 8) / 2, kb_n = (b + 1) % 2; // unit u+1
+    constexpr int st_nn = ((b + 2) % 8) / 2, kb_nn = b % 2;     // unit u+2
+    constexpr int st_p = ((b + 7) % 8) / 2, kb_p = (b + 7) % 2; // unit u-1
+    constexpr int cur = b % 2, nxt = cur ^ 1;
+
+    // ---- causal / range mask on units that cross a limit -------------------------
+    const int key0 = it.k_begin + 32 * u;
+    if (key0 + 31 > min_lim) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % KDEPTH][0], qf[kk], s[0], 0, 0, 0);
-      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % KDEPTH][1], qf[kk], s[1], 0, 0, 0);
-      if (kk + KDEPTH < KK) {
-        ka[kk % KDEPTH][0] = ldk(kbuf, kk + KDEPTH, 0);
-        ka[kk % KDEPTH][1] = ldk(kbuf, kk + KDEPTH, 1);
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+        if (key > lim) s[cur][r] = -INFINITY;
       }
-      if (kk >= KK - VDEPTH) vf[kk - (KK - VDEPTH)] = ldv(kbuf, kk - (KK - VDEPTH));
-      __builtin_amdgcn_sched_barrier(0);
     }
-  };
-
-  auto tile_step = [&](auto BUFC, int t) __attribute__((always_inline)) {
-    constexpr int buf = decltype(BUFC)::value;
-    constexpr int nbuf = (buf + 1) % NSTAGE;
-    const bool pre = t + 3 < nt;
-    const bool next = t + 1 < nt;
-    if (pre) issue_tile((buf + 3) % NSTAGE, t + 3);
-    qk_phase(buf);
-
-    // ---- causal / range mask on tiles that cross a limit -----------------------
-    const int key0 = it.k_begin + t * BN;
-    if (key0 + BN - 1 > min_lim) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-          if (key > lim) s[kb][r] = -INFINITY;
-        }
-    }
-
     // ---- running max: one query column per lane, key halves in lanes l and l^32 -----
-    {
-      float mx4[4];
+    float mx4[4];
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {  // four independent chains
-        mx4[q4] = fmaxf(s[0][q4], s[1][q4]);
-#pragma unroll
-        for (int r = 4; r < 16; r += 4) mx4[q4] = fmaxf(mx4[q4], fmaxf(s[0][r + q4], s[1][r + q4]));
-      }
-      float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
-      mx = fmaxf(mx, swap_halves(mx));
-      if (__any(mx > m_run + tau)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2((m_run - m_new) * c);
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-      }
-      mc = m_run * c;
+    for (int q4 = 0; q4 < 4; ++q4)   // four chains of three-input maxima
+      mx4[q4] = fmaxf(fmaxf(fmaxf(s[cur][q4], s[cur][4 + q4]), s[cur][8 + q4]), s[cur][12 + q4]);
+    float mx = fmaxf(fmaxf(fmaxf(mx4[0], mx4[1]), mx4[2]), mx4[3]);
+    mx = fmaxf(mx, swap_halves(mx));
+    const bool moved = __any(mx > m_run + tau);
+    float alpha = 1.0f;
+    if (moved) {
+      const float m_new = fmaxf(m_run, mx);
+      alpha = fast_exp2((m_run - m_new) * c);
+      m_run = m_new;
+      l_run *= alpha;
     }
+    mc = m_run * c;
     rs0 = 0.f;
     rs1 = 0.f;
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) exp_pair(g, j);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int r = 0; r < 16; ++r) s[nxt][r] = 0.f;
 
-    // ---- O^T += V^T P^T -----------------------------------------------------------------
 #pragma unroll
-    for (int step = 0; step < PV_STEPS; ++step) {
-      const int g = step / DB, db = step % DB;
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[step % VDEPTH], pf[g].v, o[db], 0, 0, 0);
-      if (step + VDEPTH < PV_STEPS) vf[step % VDEPTH] = ldv(buf, step + VDEPTH);
-      if (step >= PV_STEPS - KDEPTH && next) {
-        ka[step - (PV_STEPS - KDEPTH)][0] = ldk(nbuf, step - (PV_STEPS - KDEPTH), 0);
-        ka[step - (PV_STEPS - KDEPTH)][1] = ldk(nbuf, step - (PV_STEPS - KDEPTH), 1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < QS; ++i) {
+      s[nxt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[nxt], 0, 0, 0);
+      ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk_u(st_n, kb_n, i + KDEPTH) : ldk_u(st_nn, kb_nn, i + KDEPTH - QS);
+      o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[nxt].v[i / DB], o[i % DB], 0, 0, 0);
+      vf[i % VDEPTH] = (i + VDEPTH < PS) ? ldv_u(st_p, kb_p, i + VDEPTH) : ldv_u(st_c, kb_c, i + VDEPTH - PS);
+#pragma unroll
+      for (int jj = 0; jj < PPS; ++jj) exp_pair(cur, i * PPS + jj);
+    }
+    // the order wanted from the scheduler for the block above, per step: an MFMA,
+    // the K fragment read, half of the step's vector work, the other MFMA, the two
+    // transposed V reads, the rest of the vector work
+#pragma unroll
+    for (int i = 0; i < QS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);            // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // LDS read
+      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);      // vector ALU incl. transcendental
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);            // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);            // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS + 2, 0);  // vector ALU
     }
     l_run += rs0 + rs1;
-    // tile t+2 must have landed (in every wave) before the next iteration reads its
-    // K fragments ahead; the loads of tile t+3, issued above, may stay in flight
-    if (pre)
-      __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * IPW));
-    else
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-    wg_barrier();
+    // pin the vector work above to this block: without a use here the compiler
+    // sinks it below the branch that follows, away from the MFMAs it should hide under
+    asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(l_run));
+    __builtin_amdgcn_sched_barrier(0);
+    // everything accumulated so far (unit u-1 included) was scaled by the old max
+    if (moved) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
   };
 
-  // ---- prologue: tiles 0..2 into stages 0..2 ---------------------------------------
+  // ---- prologue: tiles 0 and 1 on their way, stage 3 cleared ------------------------
   issue_tile(0, 0);
   if (nt > 1) issue_tile(1, 1);
-  if (nt > 2) issue_tile(2, 2);
+  {
+    // the first unit's body multiplies V^T fragments of "unit -1" (stage 3) by zero
+    // probabilities; clear that stage so that no stale NaN pattern can leak in
+    const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < TILE_BYTES / 16 / NT; ++i) *(u32x4*)(&sv[3][(tid + NT * i) * 16]) = z;
+  }
   // Everything issued so far (the Q fragments included) must have landed before the
   // loop; a wait left to the compiler would sit inside the loop, where it would
   // also cover the loads of later tiles.
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   wg_barrier();
+
+  // S^T of unit 0 on its own, then the operand buffers as the first body expects them
 #pragma unroll
-  for (int kk = 0; kk < KDEPTH; ++kk) {
-    ka[kk][0] = ldk(0, kk, 0);
-    ka[kk][1] = ldk(0, kk, 1);
+  for (int j = 0; j < KDEPTH; ++j) ka[j] = ldk_u(0, 0, j);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[0][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < QS; ++i) {
+    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[0], 0, 0, 0);
+    ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk_u(0, 0, i + KDEPTH) : ldk_u(0, 1, i + KDEPTH - QS);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int j = 0; j < VDEPTH; ++j) vf[j] = ldv_u(3, 1, j);   // "unit -1": cleared stage
+  {
+    const bf16x2 z2 = {(__bf16)0.0f, (__bf16)0.0f};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pf[1].h[j] = z2;
   }
 
+  // iteration t = units 2t and 2t+1; tile t+2 is requested at its start and awaited
+  // at its end, before the barrier after which the next iteration starts reading it
+  auto iteration = [&](auto TC, int t) __attribute__((always_inline)) {
+    constexpr int ts = decltype(TC)::value;   // t mod 4
+    if (t + 2 < nt) issue_tile((ts + 2) % NSTAGE, t + 2);
+    unit_body(std::integral_constant<int, 2 * ts>{}, 2 * t);
+    if (2 * t + 1 < U) unit_body(std::integral_constant<int, 2 * ts + 1>{}, 2 * t + 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+2 is in LDS
+    wg_barrier();
+  };
   for (int t = 0; t < nt; t += 4) {
-    tile_step(std::integral_constant<int, 0>{}, t);
-    if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
-    if (t + 2 < nt) tile_step(std::integral_constant<int, 2>{}, t + 2);
-    if (t + 3 < nt) tile_step(std::integral_constant<int, 3>{}, t + 3);
+    iteration(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < nt) iteration(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 < nt) iteration(std::integral_constant<int, 2>{}, t + 2);
+    if (t + 3 < nt) iteration(std::integral_constant<int, 3>{}, t + 3);
+  }
+
+  // ---- drain: O^T += V^T P^T of the last unit ------------------------------------------
+  {
+    const int ul = U - 1;
+    const int st = (ul >> 1) & 3, kb = ul & 1;
+    const unsigned char* vbase_l = SV(st) + 2 * kb * 16 * ROWB;
+    auto ldv_l = [&](int j) __attribute__((always_inline)) -> bf16x8 {
+      const unsigned char* vp = vbase_l + (j / DB) * 16 * ROWB + voff[j % DB];
+      union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
+      cat.h.a = lds_read_tr16(vp);
+      cat.h.b = lds_read_tr16(vp + 8 * ROWB);
+      return cat.v;
+    };
+    // the fragments preloaded by the last body belong to this unit already
+    if (ul & 1) {
+#pragma unroll
+      for (int i = 0; i < PS; ++i) {
+        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[1].v[i / DB], o[i % DB], 0, 0, 0);
+        if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv_l(i + VDEPTH);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PS; ++i) {
+        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[0].v[i / DB], o[i % DB], 0, 0, 0);
+        if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv_l(i + VDEPTH);
+      }
+    }
   }
 
   // ---- epilogue ---------------------------------------------------------------------
