@@ -179,6 +179,18 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
                     size_t workspace_bytes, int32_t* items /* [max_items][8] */, int32_t max_items,
                     int32_t* n_items);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
+ * library is bracketed by two HIP events recorded on the launch stream (this
+ * costs a little, so leave it off in production).  oppo_profile_read waits for
+ * the recorded events, writes the summed kernel time in milliseconds and the
+ * number of launches since the last read into kernel_ms[3] / launches[3]
+ * (host arrays; index 0 = attention kernel, 1 = split-KV merge kernel,
+ * 2 = append kernel) and forgets them.  Not thread-safe.
+ */
+int oppo_profile_enable(int on);
+int oppo_profile_read(double* kernel_ms /* [3] */, int32_t* launches /* [3] */);
+
 /* Reason of the last failing call on this thread ("" if none). */
 const char* oppo_last_error(void);
 

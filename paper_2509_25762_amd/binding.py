@@ -31,6 +31,7 @@ OPT_NUM_CUS = 2
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version",
+    "oppo_profile_enable", "oppo_profile_read",
 ]
 
 
@@ -82,6 +83,10 @@ def load() -> ctypes.CDLL:
     lib.oppo_plan_debug.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, i32p, ctypes.c_size_t, i32p,
                                     ctypes.c_int32, i32p]
     lib.oppo_plan_debug.restype = ctypes.c_int
+    lib.oppo_profile_enable.argtypes = [ctypes.c_int]
+    lib.oppo_profile_enable.restype = ctypes.c_int
+    lib.oppo_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i32p]
+    lib.oppo_profile_read.restype = ctypes.c_int
     lib.oppo_last_error.argtypes = []
     lib.oppo_last_error.restype = ctypes.c_char_p
     lib.oppo_version.argtypes = []
@@ -158,6 +163,19 @@ def oppo_last_error() -> str:
 
 def oppo_set_option(option: int, value: int) -> None:
     _check(load().oppo_set_option(option, value))
+
+
+def oppo_profile_enable(on: bool) -> None:
+    _check(load().oppo_profile_enable(1 if on else 0))
+
+
+def oppo_profile_read():
+    """({'attn','merge','append'} -> kernel milliseconds, same -> launch counts) since the last read."""
+    ms = (ctypes.c_double * 3)()
+    n = (ctypes.c_int32 * 3)()
+    _check(load().oppo_profile_read(ms, n))
+    names = ("attn", "merge", "append")
+    return {k: ms[i] for i, k in enumerate(names)}, {k: n[i] for i, k in enumerate(names)}
 
 
 def oppo_chunk_schedule(prompt_len, resp_len, C: int, t: int):

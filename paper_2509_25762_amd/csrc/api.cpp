@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <functional>
 #include <vector>
 
 #include "../../include/oppo_attn.h"
@@ -30,8 +31,18 @@ struct Options {
 };
 Options g_opt;
 
-// Shortest key range worth a workgroup of its own when splitting automatically.
-constexpr int kMinSplitKeys = 256;
+// Cost model of the planner, in units of one 64-key tile of one workgroup:
+// shortest piece worth a workgroup of its own, fixed start-up + drain share of a
+// workgroup, extra cost of writing a partial result, cost of the merge kernel.
+// (Measured on MI355X: a tile takes about 2.1 us; a workgroup's start-up and
+// drain about 4 us; a partial result is 256 rows x (D + 2) floats per kv-head,
+// whose write shares HBM with all other workgroups, about 8 us; the merge kernel
+// is bound by reading those partials back, about 0.26 us per piece.)
+constexpr int kMinSplitTiles = 4;
+constexpr float kStartTiles = 2.0f;
+constexpr float kPartialTiles = 4.0f;
+constexpr float kMergeTiles = 2.0f;
+constexpr float kMergeTilesPerPiece = 0.125f;
 // Upper bound on partial slots the automatic planner may ask for, per CU.
 constexpr int kSlotsPerCu = 6;
 
@@ -102,29 +113,70 @@ void make_plan(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, siz
       tiles.push_back(t);
     }
   }
-  // target key-range length per workgroup
-  int64_t target = 0;  // 0 = no splitting
+  // Key-range length per workgroup, in 64-key tiles (0 = no splitting).  The
+  // automatic choice compares a few candidate piece lengths - cut so that the
+  // launch fills the compute units in one, two, three or four even rounds - and
+  // no splitting at all, under a small cost model: a workgroup costs its tiles
+  // plus a fixed start-up/drain share, a split piece also its partial-result
+  // write, and any split adds the merge kernel.  The estimate is the makespan of
+  // longest-first list scheduling, which is what the hardware dispatcher does
+  // with a launch sorted by length.
+  int piece_tiles = 0;
   int forced = 0;
+  auto tiles_of = [](const Tile& t) { return (t.keys + oppo::kKeyTile - 1) / oppo::kKeyTile; };
+  auto split_of = [&](int ntile, int piece) {
+    if (piece <= 0 || ntile <= piece) return 1;
+    return std::min((ntile + piece - 1) / piece, oppo::kMaxSplit);
+  };
   if (slots_avail > 0 && g_opt.split_kv != 1) {
     if (g_opt.split_kv >= 2) {
       forced = g_opt.split_kv;
     } else {
-      const int64_t wg_keys = total_keys * ls.Hkv;
-      target = std::max<int64_t>(kMinSplitKeys, wg_keys / ((int64_t)g_opt.num_cus * 3));
+      const int W = g_opt.num_cus;
+      int64_t total_tiles = 0;
+      for (const Tile& t : tiles) total_tiles += tiles_of(t);
+      total_tiles *= ls.Hkv;
+      auto makespan = [&](int piece) {
+        std::vector<float> costs;
+        size_t slots = 0;
+        for (const Tile& t : tiles) {
+          const int ntile = tiles_of(t);
+          int ns = split_of(ntile, piece);
+          if (ns > 1 && slots + ns > slots_avail) ns = 1;
+          if (ns > 1) slots += ns;
+          for (int p = 0; p < ns; ++p) {   // pieces as even as whole tiles allow
+            const int n = ntile / ns + (p < ntile % ns ? 1 : 0);
+            costs.push_back((float)n + kStartTiles + (ns > 1 ? kPartialTiles : 0.f));
+          }
+        }
+        std::sort(costs.begin(), costs.end(), [](float a, float b) { return a > b; });
+        // every piece exists once per kv-head: schedule the replicated list
+        std::vector<float> load((size_t)W, 0.f);
+        std::make_heap(load.begin(), load.end(), std::greater<float>());
+        for (float cst : costs)
+          for (int h = 0; h < ls.Hkv; ++h) {
+            std::pop_heap(load.begin(), load.end(), std::greater<float>());
+            load.back() += cst;
+            std::push_heap(load.begin(), load.end(), std::greater<float>());
+          }
+        float ms = 0.f;
+        for (float x : load) ms = std::max(ms, x);
+        return ms + (slots ? kMergeTiles + kMergeTilesPerPiece * (float)slots : 0.f);
+      };
+      float best = makespan(0);
+      for (int rounds = 1; rounds <= 4; ++rounds) {
+        const int piece = (int)std::max<int64_t>(kMinSplitTiles, (total_tiles + (int64_t)rounds * W - 1) / ((int64_t)rounds * W));
+        const float m = makespan(piece);
+        if (m < best * 0.97f) best = m, piece_tiles = piece;   // split only for a clear gain
+      }
     }
   }
   size_t next_slot = 0;
   for (const Tile& t : tiles) {
     const SeqView& s = seqs[t.seq];
-    const int ntile = (t.keys + oppo::kKeyTile - 1) / oppo::kKeyTile;
-    int nsplit = 1;
-    if (forced)
-      nsplit = std::min(forced, ntile);
-    else if (target > 0 && t.keys > target)
-      nsplit = (int)std::min<int64_t>((t.keys + target - 1) / target, ntile);
-    int per = (ntile + nsplit - 1) / nsplit;
-    nsplit = (ntile + per - 1) / per;
-    if (nsplit > 1 && next_slot + (size_t)nsplit > slots_avail) nsplit = 1, per = ntile;
+    const int ntile = tiles_of(t);
+    int nsplit = forced ? std::min(std::min(forced, ntile), oppo::kMaxSplit) : split_of(ntile, piece_tiles);
+    if (nsplit > 1 && next_slot + (size_t)nsplit > slots_avail) nsplit = 1;
     oppo::AttnItem it;
     it.kv_row0 = s.kv_row0;
     it.q_row0 = s.q_row0 + t.j0;
@@ -142,11 +194,14 @@ void make_plan(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, siz
       ci.part0 = (int32_t)next_slot;
       ci.nsplit = nsplit;
       plan->combines.push_back(ci);
-      for (int p = 0; p < nsplit; ++p) {
-        it.k_begin = p * per * oppo::kKeyTile;
-        it.k_end = std::min<int32_t>(t.keys, (p + 1) * per * oppo::kKeyTile);
+      int tile0 = 0;
+      for (int p = 0; p < nsplit; ++p) {   // pieces as even as whole tiles allow
+        const int n = ntile / nsplit + (p < ntile % nsplit ? 1 : 0);
+        it.k_begin = tile0 * oppo::kKeyTile;
+        it.k_end = std::min<int32_t>(t.keys, (tile0 + n) * oppo::kKeyTile);
         it.part = (int32_t)next_slot++;
         plan->items.push_back(it);
+        tile0 += n;
       }
     }
   }
@@ -390,6 +445,15 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
     o[6] = it.part;
     o[7] = 0;
   }
+  return OPPO_OK;
+}
+
+int oppo_profile_enable(int on) { return oppo::profile_enable(on); }
+
+int oppo_profile_read(double* kernel_ms, int32_t* launches) {
+  if (!kernel_ms || !launches) return fail(OPPO_ERR_INVALID, "null array");
+  const int e = oppo::profile_read(kernel_ms, launches);
+  if (e) return fail(OPPO_ERR_HIP, "event timing failed: %s", oppo::hip_error_string(e));
   return OPPO_OK;
 }
 

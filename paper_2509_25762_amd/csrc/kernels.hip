@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <vector>
 
 #include "oppo_internal.h"
 
@@ -510,7 +511,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   }
 }
 
-// Merge the partial (max, sum, unnormalised O) of the pieces of a split tile:
+// Merge the partial (max, sum, unnormalised O) of the pieces of a split tile
+// (at most kMaxSplit pieces):
 // out = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max_s m_s) * c).
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
@@ -523,22 +525,45 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
   const int hh = r / P.TM;
   const int tok = r - hh * P.TM;
   if (hh >= P.G || tok >= it.n_tok) return;
+  // all loads of a batch are issued before the first use, so the merge is bound
+  // by bandwidth and not by a chain of dependent memory latencies
+  const int64_t slot0 = ((int64_t)it.part0 * P.Hkv + kvh) * kTileRows + r;
+  const int64_t sstride = (int64_t)P.Hkv * kTileRows;   // slots between consecutive pieces
+  float ms[kMaxSplit], ls[kMaxSplit];
+#pragma unroll
+  for (int s = 0; s < kMaxSplit; ++s) {
+    const bool on = s < it.nsplit;
+    const float2 ml = on ? *(const float2*)(P.part_ml + (slot0 + s * sstride) * 2) : float2{-INFINITY, 0.f};
+    ms[s] = ml.x;
+    ls[s] = ml.y;
+  }
   float m_max = -INFINITY;
-  for (int s = 0; s < it.nsplit; ++s) {
-    const int64_t slot = ((int64_t)(it.part0 + s) * P.Hkv + kvh) * kTileRows + r;
-    m_max = fmaxf(m_max, P.part_ml[slot * 2]);
+#pragma unroll
+  for (int s = 0; s < kMaxSplit; ++s) m_max = fmaxf(m_max, ms[s]);
+  float l = 0.f;
+#pragma unroll
+  for (int s = 0; s < kMaxSplit; ++s) {
+    ms[s] = (s < it.nsplit) ? fast_exp2((ms[s] - m_max) * P.c) : 0.f;   // now the weight of piece s
+    l += ms[s] * ls[s];
   }
   float4 acc = {0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-  for (int s = 0; s < it.nsplit; ++s) {
-    const int64_t slot = ((int64_t)(it.part0 + s) * P.Hkv + kvh) * kTileRows + r;
-    const float w = fast_exp2((P.part_ml[slot * 2] - m_max) * P.c);
-    l += w * P.part_ml[slot * 2 + 1];
-    const float4 x = *(const float4*)(P.part_o + slot * D + d4);
-    acc.x += w * x.x;
-    acc.y += w * x.y;
-    acc.z += w * x.z;
-    acc.w += w * x.w;
+#pragma unroll
+  for (int s0 = 0; s0 < kMaxSplit; s0 += 8) {
+    if (s0 >= it.nsplit) break;
+    float4 x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int sj = min(s0 + j, it.nsplit - 1);   // clamped pieces carry weight 0 ... see below
+      x[j] = *(const float4*)(P.part_o + (slot0 + sj * sstride) * D + d4);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = (s0 + j < it.nsplit) ? ms[s0 + j] : 0.f;
+      acc.x += w * x[j].x;
+      acc.y += w * x[j].y;
+      acc.z += w * x[j].z;
+      acc.w += w * x[j].w;
+    }
   }
   const float inv = 1.0f / l;
   bf16x4 w4;
@@ -572,6 +597,48 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams P) {
 // Launchers
 // ---------------------------------------------------------------------------------
 
+// Optional per-kernel timing: HIP events recorded on the launch stream right
+// before and after each kernel launch while enabled.
+struct EventPair { hipEvent_t a, b; int kind; };
+static bool g_prof_on = false;
+static std::vector<EventPair> g_prof_events;
+
+static void prof_begin(int kind, hipStream_t st) {
+  if (!g_prof_on) return;
+  EventPair p;
+  p.kind = kind;
+  if (hipEventCreate(&p.a) != hipSuccess) return;
+  if (hipEventCreate(&p.b) != hipSuccess) {
+    (void)hipEventDestroy(p.a);
+    return;
+  }
+  (void)hipEventRecord(p.a, st);
+  g_prof_events.push_back(p);
+}
+static void prof_end(hipStream_t st) {
+  if (!g_prof_on || g_prof_events.empty()) return;
+  (void)hipEventRecord(g_prof_events.back().b, st);
+}
+int profile_enable(int on) {
+  g_prof_on = on != 0;
+  return 0;
+}
+int profile_read(double ms[3], int32_t launches[3]) {
+  for (int k = 0; k < 3; ++k) ms[k] = 0.0, launches[k] = 0;
+  int rc = 0;
+  for (EventPair& p : g_prof_events) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(p.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, p.a, p.b);
+    if (e != hipSuccess) rc = (int)e;
+    else if (p.kind >= 0 && p.kind < 3) ms[p.kind] += t, launches[p.kind] += 1;
+    (void)hipEventDestroy(p.a);
+    (void)hipEventDestroy(p.b);
+  }
+  g_prof_events.clear();
+  return rc;
+}
+
 int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
                      float* part_o, float* part_ml, const AttnItem* items, int n_items, void* stream) {
   hipStream_t st = (hipStream_t)stream;
@@ -592,10 +659,12 @@ int launch_attention(const LayerShape& ls, const void* q, const void* k, const v
     P.n_items = n;
     for (int i = 0; i < n; ++i) P.items[i] = items[base + i];
     dim3 grid((unsigned)(n * ls.Hkv));
+    prof_begin(0, st);
     if (ls.D == 128)
       hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(512), 0, st, P);
     else
       hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(512), 0, st, P);
+    prof_end(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
@@ -620,10 +689,12 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
     for (int i = 0; i < n; ++i) P.items[i] = items[base + i];
     const int rpb = 256 / (ls.D / 4);
     dim3 grid((unsigned)(n * ls.Hkv), (unsigned)(kTileRows / rpb)), block(256);
+    prof_begin(1, st);
     if (ls.D == 128)
       hipLaunchKernelGGL(combine_kernel<128>, grid, block, 0, st, P);
     else
       hipLaunchKernelGGL(combine_kernel<64>, grid, block, 0, st, P);
+    prof_end(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
@@ -649,7 +720,9 @@ int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void
     }
     (void)max_tok;
     dim3 grid((unsigned)n, (unsigned)((mt + kAppendTok - 1) / kAppendTok), 2), block(256);
+    prof_begin(2, st);
     hipLaunchKernelGGL(kv_append_kernel, grid, block, 0, st, P);
+    prof_end(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }

@@ -11,6 +11,8 @@ namespace oppo {
 constexpr int kTileRows = 256;
 // Keys per iteration of the key loop.
 constexpr int kKeyTile = 64;
+// Most pieces a query tile's key range is ever cut into.
+constexpr int kMaxSplit = 32;
 // Work descriptors travel by value in the kernel-argument segment, so the
 // host arrays are snapshotted at launch time without any staging copy.
 constexpr int kMaxAttnItems = 1000;     // 1000 * 32 B + header < 32 KiB
@@ -60,6 +62,8 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
                   const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
 const char* hip_error_string(int err);
+int profile_enable(int on);
+int profile_read(double ms[3], int32_t launches[3]);  // 0 attention, 1 merge, 2 append
 
 // Bytes of one partial slot (all kv-heads): kTileRows rows x (D + 2) floats each.
 inline size_t part_slot_bytes(int Hkv, int D) {
