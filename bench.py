@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+# HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
+# scaled by what the same counters read for the append kernel (a plain copy of known
+# size); see profiles/attn_fwd_kernel_config2.md.  Only the default workload was profiled.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 228.6e6}
 
 
 def cpu_baseline(cfg, ep, budget_s: float = 12.0):
@@ -167,7 +171,9 @@ def main() -> int:
         "frac_hbm_peak": tot_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBPS,
         "prompt_prefill_ms": prompt_ms,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.index),
+                     "algorithmic_bytes_per_launch": sum(w["kv_read_bytes"] + w["qo_bytes"] for w in work) / T,
                      "kernel": "attn_fwd_kernel",
                      "launches_per_step": launches_per_step, "avg_launch_ms": attn_total_ms / launches_per_step,
                      "first_pass": {"ms": float(attn_pass_ms[0]),
