@@ -130,7 +130,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NSTAGE = 4;
   constexpr int RPI = 1024 / ROWB;     // tile rows one wave-wide 16-byte load covers
   constexpr int IPW = BN / RPI / 8;    // such loads per wave, per tile, for K and again for V
-  constexpr int KDEPTH = 4;          // K fragments kept in flight
+  constexpr int KDEPTH = KK;         // K fragments kept in flight (a whole unit ahead)
   constexpr int VDEPTH = DB;         // V^T fragments kept in flight
   static_assert(IPW >= 1 && NT == 512, "tile smaller than the workgroup");
 
@@ -273,10 +273,11 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     return cat.v;
   };
 
-  // the running max is refreshed only when a score exceeds it by more than 2^8
-  // in the exp2 domain; until then probabilities stay below 256, which fp32
-  // sums and bf16 operands hold without loss
-  const float tau = 8.0f / c;
+  // A column's reference value m_run (the "running max" of the online softmax) is
+  // only moved when the partial row sum of a 32-key unit exceeds 2^24: the weights
+  // stay far inside the fp32 / bf16 range, relative precision does not depend on
+  // the reference, and the maximum is not needed on the common path.
+  constexpr float kRowSumLimit = 16777216.0f;
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
   // ------------------------------------------------------------------------------
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   bf16x8 ka[KDEPTH];                             // K fragments in flight: step j of a unit sits in ka[j % KDEPTH]
   bf16x8 vf[VDEPTH];                             // V^T fragments in flight, likewise
   union { bf16x2 h[8]; bf16x8 v[2]; } pf[2];     // pf[u & 1] = probabilities of unit u, B-operand layout
-  float mc = 0.f, rs0 = 0.f, rs1 = 0.f;
+  float mc = m_run * c, rs0 = 0.f, rs1 = 0.f;
 
   const int U = (k_hi - it.k_begin + 31) / 32;   // units of this item
 
@@ -308,17 +309,25 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   // probabilities 2p, 2p+1 of the unit in s[cur]: exp2, round to bf16, add to the
   // row sum (the sum uses the rounded values, like the numerator does)
+  // The two empty asm statements pin the work to its place in the instruction
+  // stream: the inputs only "exist" after the first, the results are "used" by
+  // the second, and such statements keep their order.
   auto exp_pair = [&](int cur, int pr) __attribute__((always_inline)) {
-    const float p0 = fast_exp2(fmaf(s[cur][2 * pr], c, -mc));
-    const float p1 = fast_exp2(fmaf(s[cur][2 * pr + 1], c, -mc));
+    float x0 = s[cur][2 * pr], x1 = s[cur][2 * pr + 1];
+    asm volatile("" : "+v"(x0), "+v"(x1));
+    const float p0 = fast_exp2(fmaf(x0, c, -mc));
+    const float p1 = fast_exp2(fmaf(x1, c, -mc));
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
-    pf[cur].h[pr] = pk;
-    if (pr & 1)
+    if (pr & 1) {
       rs1 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, rs1, false);
-    else
+      asm volatile("" : "+v"(pk), "+v"(rs1));
+    } else {
       rs0 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, rs0, false);
+      asm volatile("" : "+v"(pk), "+v"(rs0));
+    }
+    pf[cur].h[pr] = pk;
   };
 
   auto unit_body = [&](auto BC, int u) __attribute__((always_inline)) {
@@ -338,22 +347,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
         if (key > lim) s[cur][r] = -INFINITY;
       }
     }
-    // ---- running max: one query column per lane, key halves in lanes l and l^32 -----
-    float mx4[4];
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4)   // four chains of three-input maxima
-      mx4[q4] = fmaxf(fmaxf(fmaxf(s[cur][q4], s[cur][4 + q4]), s[cur][8 + q4]), s[cur][12 + q4]);
-    float mx = fmaxf(fmaxf(fmaxf(mx4[0], mx4[1]), mx4[2]), mx4[3]);
-    mx = fmaxf(mx, swap_halves(mx));
-    const bool moved = __any(mx > m_run + tau);
-    float alpha = 1.0f;
-    if (moved) {
-      const float m_new = fmaxf(m_run, mx);
-      alpha = fast_exp2((m_run - m_new) * c);
-      m_run = m_new;
-      l_run *= alpha;
-    }
-    mc = m_run * c;
+    // The probabilities of this unit are formed against the reference value m_run
+    // the column already has (no maximum is taken first); only if a row sum comes
+    // out too large - always for a column's first visible keys, otherwise almost
+    // never - the unit is redone against its true maximum, see below.
     rs0 = 0.f;
     rs1 = 0.f;
 #pragma unroll
@@ -367,31 +364,49 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       vf[i % VDEPTH] = (i + VDEPTH < PS) ? ldv_u(st_p, kb_p, i + VDEPTH) : ldv_u(st_c, kb_c, i + VDEPTH - PS);
 #pragma unroll
       for (int jj = 0; jj < PPS; ++jj) exp_pair(cur, i * PPS + jj);
+      // within the step: an MFMA, the K fragment read, half of the vector work, the
+      // other MFMA, the two transposed V reads, the rest of the vector work
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // the order wanted from the scheduler for the block above, per step: an MFMA,
-    // the K fragment read, half of the step's vector work, the other MFMA, the two
-    // transposed V reads, the rest of the vector work
-#pragma unroll
-    for (int i = 0; i < QS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);            // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // LDS read
-      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);      // vector ALU incl. transcendental
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);            // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);            // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS + 2, 0);  // vector ALU
-    }
-    l_run += rs0 + rs1;
+    float rs = rs0 + rs1;
     // pin the vector work above to this block: without a use here the compiler
     // sinks it below the branch that follows, away from the MFMAs it should hide under
-    asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(l_run));
+    asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(rs));
     __builtin_amdgcn_sched_barrier(0);
-    // everything accumulated so far (unit u-1 included) was scaled by the old max
-    if (moved) {
+    if (__any(rs > kRowSumLimit)) {
+      // Some column saw a score far above its reference (or has no reference yet):
+      // take the unit's true maximum (one query column per lane, its key halves in
+      // lanes l and l^32), move every column's reference up to it, redo the unit's
+      // probabilities, and rescale what has been accumulated so far - unit u-1
+      // included, whose MFMAs above still used the old reference.
+      float mx4[4];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        mx4[q4] = fmaxf(fmaxf(fmaxf(s[cur][q4], s[cur][4 + q4]), s[cur][8 + q4]), s[cur][12 + q4]);
+      float mx = fmaxf(fmaxf(fmaxf(mx4[0], mx4[1]), mx4[2]), mx4[3]);
+      mx = fmaxf(mx, swap_halves(mx));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = fast_exp2((m_run - m_new) * c);
+      m_run = m_new;
+      mc = m_run * c;
+      l_run *= alpha;
+      rs0 = 0.f;
+      rs1 = 0.f;
+#pragma unroll
+      for (int pr = 0; pr < 8; ++pr) exp_pair(cur, pr);
+      rs = rs0 + rs1;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
     }
+    l_run += rs;
   };
 
   // ---- prologue: tiles 0 and 1 on their way, stage 3 cleared ------------------------
