@@ -150,12 +150,16 @@ size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32
  * Tuning knobs, process-wide, read at call time (not thread-safe against
  * concurrent calls).  They change how work is cut and ordered, never what is
  * computed; tests use them to show that results do not depend on the cut.
- *   OPPO_OPT_SPLIT_KV : 0 = automatic (default), 1 = never split, n >= 2 =
- *                       cut every key range into up to n pieces when a
- *                       workspace is given.
- *   OPPO_OPT_ORDER    : 0 = longest work first (default), 1 = input order,
+ *   OPPO_OPT_SPLIT_KV : 0 = automatic (default: key ranges are cut where that
+ *                       evens out the load of the persistent workgroups),
+ *                       1 = never split, n >= 2 = cut every key range into up
+ *                       to n pieces when a workspace is given.
+ *   OPPO_OPT_ORDER    : order of the pieces within a workgroup's queue:
+ *                       0 = longest first (default), 1 = input order,
  *                       2 = shortest first.
- *   OPPO_OPT_NUM_CUS  : compute units the planner balances for (default 256).
+ *   OPPO_OPT_NUM_CUS  : compute units the planner fills (default 256); the
+ *                       attention launch has num_cus / Hkv workgroups (queues)
+ *                       per kv-head, at least 1 and at most 256.
  * Returns OPPO_ERR_INVALID for an unknown option or a negative value.
  */
 typedef enum {
@@ -169,11 +173,12 @@ int oppo_set_option(int option, int value);
  * Diagnostic: the work list oppo_chunk_prefill_attn would build for a pass whose
  * sequences have kv_before[i] cached tokens and q_len[i] new rows (host arrays
  * [B]), given workspace_bytes of workspace.  Nothing is enqueued; no GPU needed.
- * items receives 8 int32 per workgroup item, in launch order:
+ * items receives 8 int32 per piece of work, grouped by queue and in the order
+ * a queue's workgroup runs them:
  *   {sequence index, first q row, tokens in tile, position of first token,
- *    first key, one past last key, partial slot or -1, 0}
+ *    first key, one past last key, partial slot or -1, queue}
  * n_items receives the count; OPPO_ERR_INVALID if it exceeds max_items.
- * Each item is replicated over the kv-heads at launch.
+ * Every queue exists once per kv-head at launch.
  */
 int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_before, const int32_t* q_len,
                     size_t workspace_bytes, int32_t* items /* [max_items][8] */, int32_t max_items,

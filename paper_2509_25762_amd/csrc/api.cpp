@@ -26,23 +26,22 @@ int fail(int code, const char* fmt, ...) {
 
 struct Options {
   int split_kv = 0;   // 0 auto, 1 off, n>=2 forced
-  int order = 0;      // 0 longest first, 1 input order, 2 shortest first
+  int order = 0;      // within a queue: 0 longest first, 1 input order, 2 shortest first
   int num_cus = 256;
 };
 Options g_opt;
 
-// Cost model of the planner, in units of one 64-key tile of one workgroup:
-// shortest piece worth a workgroup of its own, fixed start-up + drain share of a
-// workgroup, extra cost of writing a partial result, cost of the merge kernel.
-// (Measured on MI355X: a tile takes about 2.1 us; a workgroup's start-up and
-// drain about 4 us; a partial result is 256 rows x (D + 2) floats per kv-head,
-// whose write shares HBM with all other workgroups, about 8 us; the merge kernel
-// is bound by reading those partials back, about 0.26 us per piece.)
-constexpr int kMinSplitTiles = 4;
-constexpr float kStartTiles = 2.0f;
-constexpr float kPartialTiles = 4.0f;
-constexpr float kMergeTiles = 2.0f;
+// Cost model of the planner, in units of one 64-key tile of one workgroup
+// (about 2 us on MI355X): what a piece costs beyond its tiles (switching the
+// pipeline over to it), what a partial result costs on top (256 rows x (D + 2)
+// floats per kv-head written out), and the merge kernel (a launch of its own
+// plus reading the partials back).
+constexpr float kPieceTiles = 0.75f;
+constexpr float kPartialTiles = 0.5f;
+constexpr float kMergeTiles = 3.0f;
 constexpr float kMergeTilesPerPiece = 0.125f;
+// Shortest piece the stream cut makes on purpose.
+constexpr int kMinPieceTiles = 2;
 // Upper bound on partial slots the automatic planner may ask for, per CU.
 constexpr int kSlotsPerCu = 6;
 
@@ -88,130 +87,214 @@ struct SeqView {
   int32_t kv_before;
 };
 
+// One launch of the attention kernel: pieces grouped by queue.
 struct Plan {
-  std::vector<oppo::AttnItem> items;
+  std::vector<oppo::AttnItem> pieces;
+  std::vector<uint16_t> first;   // queue j runs pieces first[j] .. first[j+1]-1
   std::vector<oppo::CombineItem> combines;
 };
 
-// Cut every sequence's chunk into query tiles, split long key ranges when the
-// launch would otherwise leave compute units idle (the thin tail passes of a
-// long-tailed batch), and order the pieces longest first so that the hardware
-// dispatcher, which hands workgroups out in index order, balances them.
-void make_plan(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, size_t slots_avail, Plan* plan) {
-  struct Tile { int seq; int32_t j0, n_tok, keys; };
-  std::vector<Tile> tiles;
-  int64_t total_keys = 0;
+int queue_count(const oppo::LayerShape& ls) {
+  return std::max(1, std::min(g_opt.num_cus / ls.Hkv, oppo::kMaxQueues));
+}
+
+// A query tile: TM tokens of one sequence against all keys it may see.
+struct QTile { int seq; int32_t j0, n_tok, keys, ntile; };
+
+// Plan one launch for the query tiles [lo, hi).
+//
+// The kernel runs one persistent workgroup per (queue, kv-head); the planner
+// decides which pieces each queue runs.  Two ways of filling the queues are
+// priced with the cost model above and the cheaper one is taken:
+//   * whole tiles, longest first onto the least loaded queue - no partial
+//     results, but the longest tile bounds the makespan and with few tiles per
+//     queue the loads are uneven (the thin tail passes of a long-tailed batch);
+//   * the tiles' key ranges laid end to end and cut into equal shares, one per
+//     queue: a tile that straddles a cut is split there (on a 64-key boundary)
+//     and its pieces are merged afterwards.  A cut that falls close to a tile
+//     edge moves to the edge.
+void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, const std::vector<QTile>& tiles,
+                 size_t lo, size_t hi, size_t slots_avail, size_t* next_slot, Plan* plan) {
+  const int Q = queue_count(ls);
+  const size_t n = hi - lo;
+  struct Piece { int tile; int t0, t1; int queue; };   // tiles [t0, t1) of query tile `tile`
+  auto price = [&](const std::vector<Piece>& pcs, int nq, size_t* n_partial) {
+    std::vector<float> load((size_t)nq, 0.f);
+    size_t np = 0;
+    for (const Piece& pc : pcs) {
+      const bool whole = pc.t0 == 0 && pc.t1 == tiles[pc.tile].ntile;
+      load[pc.queue] += (float)(pc.t1 - pc.t0) + kPieceTiles + (whole ? 0.f : kPartialTiles);
+      np += whole ? 0 : 1;
+    }
+    float ms = 0.f;
+    for (float x : load) ms = std::max(ms, x);
+    if (n_partial) *n_partial = np;
+    return ms + (np ? kMergeTiles + kMergeTilesPerPiece * (float)np : 0.f);
+  };
+  // longest first onto the least loaded queue
+  auto list_schedule = [&](std::vector<Piece>& pcs) {
+    std::vector<size_t> idx(pcs.size());
+    for (size_t i = 0; i < idx.size(); ++i) idx[i] = i;
+    std::stable_sort(idx.begin(), idx.end(), [&](size_t a, size_t b) {
+      return pcs[a].t1 - pcs[a].t0 > pcs[b].t1 - pcs[b].t0;
+    });
+    typedef std::pair<float, int> Load;
+    std::vector<Load> heap;
+    for (int j = 0; j < Q; ++j) heap.push_back(Load(0.f, j));
+    auto later = [](const Load& a, const Load& b) { return a.first > b.first || (a.first == b.first && a.second > b.second); };
+    std::make_heap(heap.begin(), heap.end(), later);
+    for (size_t i : idx) {
+      std::pop_heap(heap.begin(), heap.end(), later);
+      pcs[i].queue = heap.back().second;
+      heap.back().first += (float)(pcs[i].t1 - pcs[i].t0) + kPieceTiles;
+      std::push_heap(heap.begin(), heap.end(), later);
+    }
+  };
+
+  const size_t slots_left = slots_avail > *next_slot ? slots_avail - *next_slot : 0;
+  std::vector<Piece> chosen;
+  if (g_opt.split_kv >= 2 && slots_left > 0) {
+    // forced: every tile in (up to) that many even pieces
+    size_t used = 0;
+    for (size_t i = lo; i < hi; ++i) {
+      const int nt = tiles[i].ntile;
+      int ns = std::min(std::min(g_opt.split_kv, nt), oppo::kMaxSplit);
+      if (ns > 1 && used + (size_t)ns > slots_left) ns = 1;
+      if (ns > 1) used += (size_t)ns;
+      int t0 = 0;
+      for (int p = 0; p < ns; ++p) {
+        const int len = nt / ns + (p < nt % ns ? 1 : 0);
+        chosen.push_back(Piece{(int)i, t0, t0 + len, 0});
+        t0 += len;
+      }
+    }
+    list_schedule(chosen);
+  } else {
+    for (size_t i = lo; i < hi; ++i) chosen.push_back(Piece{(int)i, 0, tiles[i].ntile, 0});
+    list_schedule(chosen);
+    if (g_opt.split_kv == 0 && slots_left > 0) {
+      const float whole_cost = price(chosen, Q, nullptr);
+      int64_t total = 0;
+      int longest = 0;
+      for (size_t i = lo; i < hi; ++i) total += tiles[i].ntile, longest = std::max(longest, tiles[i].ntile);
+      const int min_piece = std::max(kMinPieceTiles, (longest + oppo::kMaxSplit - 2) / (oppo::kMaxSplit - 1));
+      const int nq = (int)std::max<int64_t>(1, std::min<int64_t>(Q, total / min_piece));
+      std::vector<Piece> cut;
+      int64_t off = 0;      // stream position of the current tile's first key tile
+      int64_t prev = 0;     // previous cut
+      size_t i = lo;
+      for (int j = 0; j < nq; ++j) {
+        int64_t b = (j + 1 == nq) ? total : (total * (j + 1)) / nq;
+        // find the tile the cut falls into and move the cut to an edge that is close
+        {
+          int64_t o2 = off;
+          size_t i2 = i;
+          while (i2 < hi && o2 + tiles[i2].ntile <= b) o2 += tiles[i2].ntile, ++i2;
+          if (i2 < hi) {
+            const int64_t into = b - o2, rest = o2 + tiles[i2].ntile - b;
+            if (into > 0 && into < min_piece) b = o2;
+            else if (into > 0 && rest < min_piece) b = o2 + tiles[i2].ntile;
+          }
+        }
+        b = std::max(b, prev);
+        // hand [prev, b) to queue j
+        int64_t pos = prev;
+        while (pos < b) {
+          const int64_t end = std::min<int64_t>(b, off + tiles[i].ntile);
+          cut.push_back(Piece{(int)i, (int)(pos - off), (int)(end - off), j});
+          pos = end;
+          if (end == off + tiles[i].ntile) off += tiles[i].ntile, ++i;
+        }
+        prev = b;
+      }
+      size_t n_partial = 0;
+      const float cut_cost = price(cut, nq, &n_partial);
+      if (n_partial <= slots_left && cut_cost < 0.97f * whole_cost) chosen.swap(cut);
+    }
+  }
+
+  // order within a queue: longest first, input order, or shortest first
+  std::vector<size_t> idx(chosen.size());
+  for (size_t i = 0; i < idx.size(); ++i) idx[i] = i;
+  auto len_of = [&](size_t a) { return chosen[a].t1 - chosen[a].t0; };
+  std::stable_sort(idx.begin(), idx.end(), [&](size_t a, size_t b) {
+    if (chosen[a].queue != chosen[b].queue) return chosen[a].queue < chosen[b].queue;
+    if (g_opt.order == 1) return a < b;
+    if (g_opt.order == 2) return len_of(a) < len_of(b);
+    return len_of(a) > len_of(b);
+  });
+  // partial slots: the pieces of a tile take consecutive slots in key order
+  std::vector<int32_t> slot_of(chosen.size(), -1);
+  {
+    std::vector<std::vector<size_t>> by_tile(n);
+    for (size_t a = 0; a < chosen.size(); ++a) by_tile[chosen[a].tile - lo].push_back(a);
+    for (size_t t = 0; t < n; ++t) {
+      std::vector<size_t>& v = by_tile[t];
+      if (v.size() < 2) continue;
+      std::sort(v.begin(), v.end(), [&](size_t a, size_t b) { return chosen[a].t0 < chosen[b].t0; });
+      const QTile& qt = tiles[lo + t];
+      oppo::CombineItem ci;
+      ci.q_row0 = seqs[qt.seq].q_row0 + qt.j0;
+      ci.n_tok = qt.n_tok;
+      ci.part0 = (int32_t)*next_slot;
+      ci.nsplit = (int32_t)v.size();
+      plan->combines.push_back(ci);
+      for (size_t a : v) slot_of[a] = (int32_t)(*next_slot)++;
+    }
+  }
+  int queue_prev = -1;
+  for (size_t a : idx) {
+    const Piece& pc = chosen[a];
+    const QTile& qt = tiles[pc.tile];
+    const SeqView& s = seqs[qt.seq];
+    if (pc.queue != queue_prev) plan->first.push_back((uint16_t)plan->pieces.size());   // empty queues vanish
+    queue_prev = pc.queue;
+    oppo::AttnItem it;
+    it.kv_row0 = s.kv_row0;
+    it.q_row0 = s.q_row0 + qt.j0;
+    it.n_tok = qt.n_tok;
+    it.pos0 = s.kv_before + qt.j0;
+    it.k_begin = pc.t0 * oppo::kKeyTile;
+    it.k_end = std::min<int32_t>(qt.keys, pc.t1 * oppo::kKeyTile);
+    it.part = slot_of[a];
+    plan->pieces.push_back(it);
+  }
+  plan->first.push_back((uint16_t)plan->pieces.size());
+}
+
+// Cut every sequence's chunk into query tiles and plan the launches (one, unless
+// the work list outgrows the kernel-argument segment).
+void make_plans(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, size_t slots_avail,
+                std::vector<Plan>* plans) {
+  std::vector<QTile> tiles;
   for (size_t i = 0; i < seqs.size(); ++i) {
     const SeqView& s = seqs[i];
     for (int32_t j0 = 0; j0 < s.q_len; j0 += ls.TM) {
-      Tile t;
+      QTile t;
       t.seq = (int)i;
       t.j0 = j0;
       t.n_tok = std::min(ls.TM, s.q_len - j0);
       t.keys = s.kv_before + j0 + t.n_tok;
-      total_keys += t.keys;
+      t.ntile = (t.keys + oppo::kKeyTile - 1) / oppo::kKeyTile;
       tiles.push_back(t);
     }
   }
-  // Key-range length per workgroup, in 64-key tiles (0 = no splitting).  The
-  // automatic choice compares a few candidate piece lengths - cut so that the
-  // launch fills the compute units in one, two, three or four even rounds - and
-  // no splitting at all, under a small cost model: a workgroup costs its tiles
-  // plus a fixed start-up/drain share, a split piece also its partial-result
-  // write, and any split adds the merge kernel.  The estimate is the makespan of
-  // longest-first list scheduling, which is what the hardware dispatcher does
-  // with a launch sorted by length.
-  int piece_tiles = 0;
-  int forced = 0;
-  auto tiles_of = [](const Tile& t) { return (t.keys + oppo::kKeyTile - 1) / oppo::kKeyTile; };
-  auto split_of = [&](int ntile, int piece) {
-    if (piece <= 0 || ntile <= piece) return 1;
-    return std::min((ntile + piece - 1) / piece, oppo::kMaxSplit);
-  };
-  if (slots_avail > 0 && g_opt.split_kv != 1) {
-    if (g_opt.split_kv >= 2) {
-      forced = g_opt.split_kv;
-    } else {
-      const int W = g_opt.num_cus;
-      int64_t total_tiles = 0;
-      for (const Tile& t : tiles) total_tiles += tiles_of(t);
-      total_tiles *= ls.Hkv;
-      auto makespan = [&](int piece) {
-        std::vector<float> costs;
-        size_t slots = 0;
-        for (const Tile& t : tiles) {
-          const int ntile = tiles_of(t);
-          int ns = split_of(ntile, piece);
-          if (ns > 1 && slots + ns > slots_avail) ns = 1;
-          if (ns > 1) slots += ns;
-          for (int p = 0; p < ns; ++p) {   // pieces as even as whole tiles allow
-            const int n = ntile / ns + (p < ntile % ns ? 1 : 0);
-            costs.push_back((float)n + kStartTiles + (ns > 1 ? kPartialTiles : 0.f));
-          }
-        }
-        std::sort(costs.begin(), costs.end(), [](float a, float b) { return a > b; });
-        // every piece exists once per kv-head: schedule the replicated list
-        std::vector<float> load((size_t)W, 0.f);
-        std::make_heap(load.begin(), load.end(), std::greater<float>());
-        for (float cst : costs)
-          for (int h = 0; h < ls.Hkv; ++h) {
-            std::pop_heap(load.begin(), load.end(), std::greater<float>());
-            load.back() += cst;
-            std::push_heap(load.begin(), load.end(), std::greater<float>());
-          }
-        float ms = 0.f;
-        for (float x : load) ms = std::max(ms, x);
-        return ms + (slots ? kMergeTiles + kMergeTilesPerPiece * (float)slots : 0.f);
-      };
-      float best = makespan(0);
-      for (int rounds = 1; rounds <= 4; ++rounds) {
-        const int piece = (int)std::max<int64_t>(kMinSplitTiles, (total_tiles + (int64_t)rounds * W - 1) / ((int64_t)rounds * W));
-        const float m = makespan(piece);
-        if (m < best * 0.97f) best = m, piece_tiles = piece;   // split only for a clear gain
-      }
-    }
-  }
+  // a launch holds at most kMaxAttnItems pieces; cutting adds fewer than one piece per queue
+  const size_t per_launch = (size_t)(oppo::kMaxAttnItems - queue_count(ls));
   size_t next_slot = 0;
-  for (const Tile& t : tiles) {
-    const SeqView& s = seqs[t.seq];
-    const int ntile = tiles_of(t);
-    int nsplit = forced ? std::min(std::min(forced, ntile), oppo::kMaxSplit) : split_of(ntile, piece_tiles);
-    if (nsplit > 1 && next_slot + (size_t)nsplit > slots_avail) nsplit = 1;
-    oppo::AttnItem it;
-    it.kv_row0 = s.kv_row0;
-    it.q_row0 = s.q_row0 + t.j0;
-    it.n_tok = t.n_tok;
-    it.pos0 = s.kv_before + t.j0;
-    if (nsplit == 1) {
-      it.k_begin = 0;
-      it.k_end = t.keys;
-      it.part = -1;
-      plan->items.push_back(it);
-    } else {
-      oppo::CombineItem ci;
-      ci.q_row0 = it.q_row0;
-      ci.n_tok = it.n_tok;
-      ci.part0 = (int32_t)next_slot;
-      ci.nsplit = nsplit;
-      plan->combines.push_back(ci);
-      int tile0 = 0;
-      for (int p = 0; p < nsplit; ++p) {   // pieces as even as whole tiles allow
-        const int n = ntile / nsplit + (p < ntile % nsplit ? 1 : 0);
-        it.k_begin = tile0 * oppo::kKeyTile;
-        it.k_end = std::min<int32_t>(t.keys, (tile0 + n) * oppo::kKeyTile);
-        it.part = (int32_t)next_slot++;
-        plan->items.push_back(it);
-        tile0 += n;
-      }
+  for (size_t lo = 0; lo < tiles.size(); lo += per_launch) {
+    plans->emplace_back();
+    Plan* plan = &plans->back();
+    const size_t hi = std::min(tiles.size(), lo + per_launch);
+    plan_launch(ls, seqs, tiles, lo, hi, slots_avail, &next_slot, plan);
+    if (plan->pieces.size() > (size_t)oppo::kMaxAttnItems) {   // forced splitting of a long list
+      const int keep = g_opt.split_kv;
+      g_opt.split_kv = 1;
+      *plan = Plan();
+      plan_launch(ls, seqs, tiles, lo, hi, slots_avail, &next_slot, plan);
+      g_opt.split_kv = keep;
     }
   }
-  auto keys_of = [](const oppo::AttnItem& a) { return a.k_end - a.k_begin; };
-  if (g_opt.order == 0)
-    std::stable_sort(plan->items.begin(), plan->items.end(),
-                     [&](const oppo::AttnItem& a, const oppo::AttnItem& b) { return keys_of(a) > keys_of(b); });
-  else if (g_opt.order == 2)
-    std::stable_sort(plan->items.begin(), plan->items.end(),
-                     [&](const oppo::AttnItem& a, const oppo::AttnItem& b) { return keys_of(a) < keys_of(b); });
 }
 
 int run_attention(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, const void* q, const void* k,
@@ -225,13 +308,16 @@ int run_attention(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, 
     part_o = (float*)workspace;
     part_ml = part_o + slots * (size_t)ls.Hkv * oppo::kTileRows * (size_t)ls.D;
   }
-  Plan plan;
-  make_plan(ls, seqs, slots, &plan);
-  if (plan.items.empty()) return OPPO_OK;
-  int e = oppo::launch_attention(ls, q, k, v, out, part_o, part_ml, plan.items.data(), (int)plan.items.size(), stream);
-  if (e) return fail(OPPO_ERR_HIP, "attention launch failed: %s", oppo::hip_error_string(e));
-  if (!plan.combines.empty()) {
-    e = oppo::launch_combine(ls, out, part_o, part_ml, plan.combines.data(), (int)plan.combines.size(), stream);
+  std::vector<Plan> plans;
+  make_plans(ls, seqs, slots, &plans);
+  for (const Plan& plan : plans) {
+    const int e = oppo::launch_attention(ls, q, k, v, out, part_o, part_ml, plan.pieces.data(), (int)plan.pieces.size(),
+                                         plan.first.data(), (int)plan.first.size() - 1, stream);
+    if (e) return fail(OPPO_ERR_HIP, "attention launch failed: %s", oppo::hip_error_string(e));
+  }
+  for (const Plan& plan : plans) {
+    if (plan.combines.empty()) continue;
+    const int e = oppo::launch_combine(ls, out, part_o, part_ml, plan.combines.data(), (int)plan.combines.size(), stream);
     if (e) return fail(OPPO_ERR_HIP, "combine launch failed: %s", oppo::hip_error_string(e));
   }
   return OPPO_OK;
@@ -354,6 +440,8 @@ int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cac
   }
   rc = check_workspace(ls, workspace, workspace_bytes);
   if (rc) return rc;
+  if ((int64_t)cu_q[B] * ls.Hq > INT32_MAX)
+    return fail(OPPO_ERR_UNSUPPORTED, "%d query rows x %d heads exceed the 32-bit row index of the kernel", cu_q[B], ls.Hq);
   if (seqs.empty()) return OPPO_OK;
   if (!cache->k || !cache->v || !q || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
   return run_attention(ls, seqs, q, cache->k, cache->v, out, workspace, workspace_bytes, stream);
@@ -369,6 +457,8 @@ int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B, const int32_t* 
   if (rc) return rc;
   rc = check_workspace(ls, workspace, workspace_bytes);
   if (rc) return rc;
+  if ((int64_t)cu_seq[B] * ls.Hq > INT32_MAX)
+    return fail(OPPO_ERR_UNSUPPORTED, "%d rows x %d heads exceed the 32-bit row index of the kernel", cu_seq[B], ls.Hq);
   std::vector<SeqView> seqs;
   for (int32_t i = 0; i < B; ++i) {
     const int32_t n = cu_seq[i + 1] - cu_seq[i];
@@ -429,21 +519,29 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
     }
     row += q_len[i];
   }
-  Plan plan;
-  make_plan(ls, seqs, workspace_bytes / oppo::part_slot_bytes(ls.Hkv, ls.D), &plan);
-  *n_items = (int32_t)plan.items.size();
-  if ((int32_t)plan.items.size() > max_items) return fail(OPPO_ERR_INVALID, "plan has %zu items", plan.items.size());
-  for (size_t i = 0; i < plan.items.size(); ++i) {
-    const oppo::AttnItem& it = plan.items[i];
-    int32_t* o = items + 8 * i;
-    o[0] = (int32_t)it.kv_row0;
-    o[1] = it.q_row0;
-    o[2] = it.n_tok;
-    o[3] = it.pos0;
-    o[4] = it.k_begin;
-    o[5] = it.k_end;
-    o[6] = it.part;
-    o[7] = 0;
+  std::vector<Plan> plans;
+  make_plans(ls, seqs, workspace_bytes / oppo::part_slot_bytes(ls.Hkv, ls.D), &plans);
+  size_t total = 0;
+  for (const Plan& plan : plans) total += plan.pieces.size();
+  *n_items = (int32_t)total;
+  if ((int64_t)total > max_items) return fail(OPPO_ERR_INVALID, "plan has %zu pieces", total);
+  size_t w = 0;
+  int32_t queue0 = 0;
+  for (const Plan& plan : plans) {
+    for (size_t j = 0; j + 1 < plan.first.size(); ++j)
+      for (size_t i = plan.first[j]; i < plan.first[j + 1]; ++i, ++w) {
+        const oppo::AttnItem& it = plan.pieces[i];
+        int32_t* o = items + 8 * w;
+        o[0] = (int32_t)it.kv_row0;
+        o[1] = it.q_row0;
+        o[2] = it.n_tok;
+        o[3] = it.pos0;
+        o[4] = it.k_begin;
+        o[5] = it.k_end;
+        o[6] = it.part;
+        o[7] = queue0 + (int32_t)j;
+      }
+    queue0 += (int32_t)plan.first.size() - 1;
   }
   return OPPO_OK;
 }

@@ -39,7 +39,8 @@ struct AttnParams {
   float* part_ml;
   int32_t Hq, Hkv, G, TM;
   float c;
-  int32_t n_items;
+  int32_t n_queues;
+  uint16_t first[kMaxQueues + 1];   // queue j runs pieces first[j] .. first[j+1]-1, in that order
   AttnItem items[kMaxAttnItems];
 };
 static_assert(sizeof(AttnParams) <= 32768, "kernel arguments are kept within 32 KiB");
@@ -107,6 +108,9 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
       (s16x4 __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
 }
 
+// Persistent workgroups: the launch has one workgroup per (queue, kv-head), about
+// one per compute unit, and workgroup (queue j, kv-head g) runs the pieces
+// first[j] .. first[j+1]-1 of the work list one after the other.
 // Eight waves, each owning 32 query columns of the 256-row tile; two waves share
 // a SIMD.  On this hardware vector ALU instructions hide under MFMAs only when
 // the two are mixed finely (a handful of vector instructions per MFMA), so the
@@ -114,9 +118,13 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 // main loop.  Operand fragments are read from LDS several steps before the MFMA
 // that consumes them (rolling register buffers ka / vf).
 // K/V tiles go straight from global memory into a ring of four LDS stages, two
-// tiles ahead: the loads of tile t+2 are issued after the barrier that opens
-// iteration t, into the stage whose last reader finished before that barrier,
-// and each wave waits for its own loads before the barrier that closes it.
+// tiles ahead: the loads of the tile two places further down the workgroup's
+// tile stream are issued after the barrier that opens an iteration, into the
+// stage whose last reader finished before that barrier, and each wave waits for
+// its own loads before the barrier that closes it.  The stream runs across piece
+// boundaries: the first two tiles of the next piece are requested during the last
+// two iterations of the current one, and the next piece's Q fragments are
+// requested as soon as the current piece's last S^T MFMA has been issued.
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = 512;            // threads
@@ -139,55 +147,58 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // instructions take 16-bit offsets)
   __shared__ __attribute__((aligned(1024))) unsigned char sk[NSTAGE][TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sv[NSTAGE][TILE_BYTES];
-  auto SK = [&](int b) __attribute__((always_inline)) { return &sk[b][0]; };
-  auto SV = [&](int b) __attribute__((always_inline)) { return &sv[b][0]; };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int hi = lane >> 5;
-  const int kvh = blockIdx.x % P.Hkv;
-  const AttnItem it = P.items[blockIdx.x / P.Hkv];
   const int Hq = P.Hq, Hkv = P.Hkv, G = P.G, TM = P.TM;
+  const int kvh = blockIdx.x % Hkv;
+  const int queue = blockIdx.x / Hkv;
+  const int p_first = P.first[queue];
+  const int p_last = P.first[queue + 1];
+  if (p_first >= p_last) return;
   const float c = P.c;
 
-  // ---- this lane's query column ---------------------------------------------------
-  const int r_tile = wave * 32 + l32;   // row of the packed (head, token) tile
+  // The queue's piece descriptors are copied from the kernel-argument segment into
+  // LDS once: a read of that segment costs microseconds, far too much to pay at
+  // every piece boundary.
+  __shared__ __attribute__((aligned(16))) AttnItem spiece[kMaxAttnItems];
+  {
+    const u32x4* src = (const u32x4*)(P.items + p_first);
+    const int n16 = (p_last - p_first) * (int)(sizeof(AttnItem) / 16);
+    for (int i = tid; i < n16; i += NT) ((u32x4*)spiece)[i] = src[i];
+    __syncthreads();
+  }
+  // descriptor of piece p (a wave-uniform value, moved to scalar registers)
+  auto piece = [&](int p) __attribute__((always_inline)) -> AttnItem {
+    const u32x4* w = (const u32x4*)&spiece[p - p_first];
+    const u32x4 a = w[0], b = w[1];
+    AttnItem r;
+    r.kv_row0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)a[1]) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int)a[0]));
+    r.q_row0 = __builtin_amdgcn_readfirstlane((int)a[2]);
+    r.n_tok = __builtin_amdgcn_readfirstlane((int)a[3]);
+    r.pos0 = __builtin_amdgcn_readfirstlane((int)b[0]);
+    r.k_begin = __builtin_amdgcn_readfirstlane((int)b[1]);
+    r.k_end = __builtin_amdgcn_readfirstlane((int)b[2]);
+    r.part = __builtin_amdgcn_readfirstlane((int)b[3]);
+    return r;
+  };
+
+  // ---- this lane's query column (row of the packed (head, token) tile) --------------
+  const int r_tile = wave * 32 + l32;
   const int hh = r_tile / TM;
   const int tok = r_tile - hh * TM;
-  const bool valid = (hh < G) && (tok < it.n_tok);
-  const int tokc = min(tok, it.n_tok - 1);
-  const int hhc = min(hh, G - 1);
-  const int lim = min(it.pos0 + tokc, it.k_end - 1);   // last visible key of the column
-  const int64_t qoff = ((int64_t)(it.q_row0 + tokc) * Hq + kvh * G + hhc) * D;
   bf16x8 qf[KK];
-  {
-    const uint16_t* qp = P.q + qoff + hi * 8;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const bf16x8*)(qp + kk * 16);
-  }
-  // smallest limit of the workgroup's rows: tiles entirely below it need no mask
-  const int min_lim = min(it.pos0, it.k_end - 1);
-
-  f32x16 o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_run = -1e30f, l_run = 0.f;
 
   // ---- cooperative K/V tile loads ------------------------------------------------
-  const int k_hi = it.k_end;
-  const int nt = (k_hi - it.k_begin + BN - 1) / BN;
-  const int row_stride = Hkv * D;  // elements between consecutive tokens
-  const uint16_t* kbase = P.k + ((int64_t)it.kv_row0 * Hkv + kvh) * D;
-  const uint16_t* vbase = P.v + ((int64_t)it.kv_row0 * Hkv + kvh) * D;
-
   // Tiles travel global -> LDS directly (global_load_lds_dwordx4): a wave-wide
   // load drops 64 x 16 bytes at consecutive LDS addresses, i.e. RPI whole rows;
   // the LDS swizzle is applied by choosing which 16-byte granule of the row each
   // lane fetches.  Wave w moves rows (w + 8i) * RPI .. of the tile.
+  const int row_stride = Hkv * D;  // elements between consecutive tokens
   const int lrow = lane / NG;
   const int pg = lane % NG;
   uint32_t goffk[IPW], goffv[IPW];   // byte offsets of this lane's granules in a full tile
@@ -198,11 +209,84 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     goffv[i] = (uint32_t)(r * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
   }
   const uint32_t wave_rows = (uint32_t)__builtin_amdgcn_readfirstlane(wave) * 1024u;
-  auto issue_tile = [&](int stage, int t) __attribute__((always_inline)) {
-    const int key0 = it.k_begin + t * BN;
-    const int last = k_hi - 1 - key0;
-    const uint16_t* kt = kbase + (int64_t)key0 * row_stride;
-    const uint16_t* vt = vbase + (int64_t)key0 * row_stride;
+
+  // ---- the wave's staging area: turning 32 x D blocks around ----------------------
+  // A lane owns one query column, so its share of Q (a B operand) and of the output
+  // is 16-byte / 8-byte pieces of one row: moved to and from global memory like
+  // that, every instruction would touch 32 or 64 different rows.  Q and O blocks
+  // therefore travel as whole row pieces (16 bytes per lane, consecutive lanes on
+  // consecutive addresses) and are turned around in LDS, half of D at a time.  The
+  // staging area is the part of a ring stage that this very wave fills with its
+  // next tile request (2*IPW chunks of 1 KiB), used at a time when the stage's last
+  // readers have passed a barrier: no other wave is involved, no barrier needed.
+  constexpr int RB = D;             // bytes of a row per round (half a row)
+  constexpr int NS = RB / 16;       // 16-byte slots of a row per round
+  constexpr int RPC = 1024 / RB;    // rows per 1 KiB chunk
+  typedef __attribute__((address_space(3))) unsigned char* lds_ptr;
+  // row-piece side: lane handles slot lane % NS of row lane / NS of each chunk
+  const uint32_t roff = (uint32_t)((lane / NS) * RB + (((lane % NS) ^ ((lane / NS) & (NS - 1))) * 16));
+  // column side: the lane's row l32 lies in chunk l32 / RPC
+  const uint32_t coff = (uint32_t)(((l32 / RPC) % IPW) * 8192 + (l32 % RPC) * RB);
+  const uint32_t cx = (uint32_t)(l32 & (NS - 1)) * 16u;
+  auto area_of = [&](int stage, int k) __attribute__((always_inline)) -> uint32_t {   // chunk k of the area in `stage`
+    return ((k / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
+           (uint32_t)((k % IPW) * 8192);
+  };
+  auto carea_of = [&](int stage) __attribute__((always_inline)) -> uint32_t {   // chunk of the lane's own row
+    return (((l32 / RPC) / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows + coff;
+  };
+  // rows wave*32 + k*RPC + lane/NS of the packed tile -> (q-head of the group, token)
+  auto row_of = [&](int k, int* hk, int* tk) __attribute__((always_inline)) {
+    const int R0 = wave * 32 + lane / NS;
+    const int hh0 = R0 / TM;
+    int t = R0 - hh0 * TM + k * RPC, h = hh0;
+    while (t >= TM) t -= TM, ++h;
+    *hk = h;
+    *tk = t;
+  };
+  u32x4 qraw[2][2 * IPW];   // Q row pieces on their way: [half of D][chunk]
+  auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 2 * IPW; ++k) {
+      int hk, tk;
+      row_of(k, &hk, &tk);
+      // rows beyond the tile repeat a valid row; their columns are never stored
+      const uint16_t* qp = P.q + ((int64_t)(a.q_row0 + min(tk, a.n_tok - 1)) * Hq + kvh * G + min(hk, G - 1)) * D + (lane % NS) * 8;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) qraw[h][k] = *(const u32x4*)(qp + h * (D / 2));
+    }
+  };
+  auto q_collect = [&](int stage) __attribute__((always_inline)) {
+    const uint32_t cbase = carea_of(stage);
+    const uint32_t cxh = cx ^ ((uint32_t)hi * 16u);   // the lane's slots are 2*kl + hi, swizzled
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int k = 0; k < 2 * IPW; ++k)
+        *(__attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(area_of(stage, k) + roff) = qraw[h][k];
+#pragma unroll
+      for (int kl = 0; kl < KK / 2; ++kl)
+        qf[h * (KK / 2) + kl] = *(const __attribute__((address_space(3))) bf16x8*)(lds_ptr)(uintptr_t)(
+            cbase + ((uint32_t)(kl * 32) ^ cxh));
+    }
+  };
+  // The request cursor walks the workgroup's tile stream (all tiles of piece
+  // p_first, then of the next piece, ...): all of it is wave-uniform.
+  int c_piece = p_first;        // piece of the next tile to request
+  int c_left = 0;               // keys of that piece not requested yet
+  const uint16_t* c_k = nullptr;  // first row of the next tile, this kv-head
+  const uint16_t* c_v = nullptr;
+  auto cursor_open = [&]() __attribute__((always_inline)) {
+    const AttnItem a = piece(c_piece);
+    const int64_t e = (((int64_t)a.kv_row0 + a.k_begin) * Hkv + kvh) * D;
+    c_k = P.k + e;
+    c_v = P.v + e;
+    c_left = a.k_end - a.k_begin;
+  };
+  cursor_open();
+  auto issue_next = [&](int stage) __attribute__((always_inline)) {
+    if (c_piece >= p_last) return;
+    const int last = c_left - 1;
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
       uint32_t ok = goffk[i], ov = goffv[i];
@@ -212,8 +296,15 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
         ok = (uint32_t)(rc * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
         ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
       }
-      async_copy16(kt, ok, lds_addr_of(SK(stage)) + wave_rows + i * 8192u);
-      async_copy16(vt, ov, lds_addr_of(SV(stage)) + wave_rows + i * 8192u);
+      async_copy16(c_k, ok, lds_addr_of(&sk[stage][0]) + wave_rows + i * 8192u);
+      async_copy16(c_v, ov, lds_addr_of(&sv[stage][0]) + wave_rows + i * 8192u);
+    }
+    c_k += (int64_t)BN * row_stride;
+    c_v += (int64_t)BN * row_stride;
+    c_left -= BN;
+    if (c_left <= 0) {
+      ++c_piece;
+      if (c_piece < p_last) cursor_open();
     }
   };
   // workgroup barrier without the implied wait for this wave's LDS reads: the only
@@ -227,10 +318,18 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   // per-lane LDS offsets of the operand fragments (the swizzles are XORs, so they
   // are folded here once instead of per read)
-  int koff[KK];  // K fragment of k-step kk, key block 0 (block 1 is +32 rows)
+  // per-lane base pointers; stage, key half and group then are immediate offsets
+  // (made opaque to the optimiser, which would otherwise fold the array address
+  // into each read and rebuild the sum with a vector instruction every time)
+  typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
+  lds_cptr kptr[KK];   // K fragment of k-step kk, key block 0 (block 1 is +32 rows)
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) koff[kk] = l32 * ROWB + (((kk * 2 + hi) ^ (l32 % NG)) * 16);
-  int voff[DB];  // V^T fragment of d-block db, keys 4*hi.. of a 16-key group
+  for (int kk = 0; kk < KK; ++kk) {
+    uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)(l32 * ROWB + (((kk * 2 + hi) ^ (l32 % NG)) * 16));
+    asm volatile("" : "+v"(a));
+    kptr[kk] = (lds_cptr)(uintptr_t)a;
+  }
+  lds_cptr vptr[DB];   // V^T fragment of d-block db, keys 4*hi.. of a 16-key group
   {
     const int j = lane & 15;
     const int half16 = (lane >> 4) & 1;
@@ -238,35 +337,20 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       const int lg = db * 4 + 2 * half16 + ((j & 3) >> 1);
-      voff[db] = vrow * ROWB + ((lg ^ ((vrow & VSWZ_MASK) << 2)) * 16) + (j & 1) * 8;
+      uint32_t a = lds_addr_of(&sv[0][0]) + (uint32_t)(vrow * ROWB + ((lg ^ ((vrow & VSWZ_MASK) << 2)) * 16) + (j & 1) * 8);
+      asm volatile("" : "+v"(a));
+      vptr[db] = (lds_cptr)(uintptr_t)a;
     }
   }
-  // per-lane base pointers; stage, key half and group then are immediate offsets
-  // (made opaque to the optimiser, which would otherwise fold the array address
-  // into each read and rebuild the sum with a vector instruction every time)
-  typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
-  lds_cptr kptr[KK];
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)koff[kk];
-    asm volatile("" : "+v"(a));
-    kptr[kk] = (lds_cptr)(uintptr_t)a;
-  }
-  lds_cptr vptr[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    uint32_t a = lds_addr_of(&sv[0][0]) + (uint32_t)voff[db];
-    asm volatile("" : "+v"(a));
-    vptr[db] = (lds_cptr)(uintptr_t)a;
-  }
-  // K fragment (A operand of S^T = K Q^T): keys kb*32 + l32, elements kk*16 + 8*hi..
-  auto ldk = [&](int buf, int kk, int kb) __attribute__((always_inline)) -> bf16x8 {
-    return *(const __attribute__((address_space(3))) bf16x8*)(kptr[kk] + buf * TILE_BYTES + kb * 32 * ROWB);
+  // K fragment (A operand of S^T = K Q^T): keys kb*32 + l32, elements kk*16 + 8*hi..;
+  // `off` = stage * TILE_BYTES (an immediate in the main loop)
+  auto ldk = [&](int off, int kb, int kk) __attribute__((always_inline)) -> bf16x8 {
+    return *(const __attribute__((address_space(3))) bf16x8*)(kptr[kk] + off + kb * 32 * ROWB);
   };
-  // V^T fragment (A operand of O^T += V^T P^T) of PV step `step` = (16-key group g, d-block db)
-  auto ldv = [&](int buf, int step) __attribute__((always_inline)) -> bf16x8 {
-    const int g = step / DB, db = step % DB;
-    lds_cptr vp = vptr[db] + buf * TILE_BYTES + g * 16 * ROWB;
+  // V^T fragment (A operand of O^T += V^T P^T) of step j = (16-key group, d-block)
+  // of the 32-key unit (stage, kb)
+  auto ldv = [&](int off, int kb, int j) __attribute__((always_inline)) -> bf16x8 {
+    lds_cptr vp = vptr[j % DB] + off + (2 * kb + j / DB) * 16 * ROWB;
     union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
     cat.h.a = lds_read_tr16_l(vp);
     cat.h.b = lds_read_tr16_l(vp + 8 * ROWB);
@@ -293,19 +377,17 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int PPS = 8 / QS;     // probability pairs handled per step
   static_assert(QS == PS && QS % KDEPTH == 0 && PS % VDEPTH == 0, "pipeline shape");
 
+  f32x16 o[DB];
   f32x16 s[2];                                   // s[u & 1] = S^T of unit u
   bf16x8 ka[KDEPTH];                             // K fragments in flight: step j of a unit sits in ka[j % KDEPTH]
   bf16x8 vf[VDEPTH];                             // V^T fragments in flight, likewise
   union { bf16x2 h[8]; bf16x8 v[2]; } pf[2];     // pf[u & 1] = probabilities of unit u, B-operand layout
-  float mc = m_run * c, rs0 = 0.f, rs1 = 0.f;
+  float m_run, l_run, mc, rs0 = 0.f, rs1 = 0.f;
 
-  const int U = (k_hi - it.k_begin + 31) / 32;   // units of this item
-
-  // fragment of unit (stage st, key half kb): K step kk, or V step j = group * DB + d-block
-  auto ldk_u = [&](int st, int kb, int kk) __attribute__((always_inline)) -> bf16x8 { return ldk(st, kk, kb); };
-  auto ldv_u = [&](int st, int kb, int j) __attribute__((always_inline)) -> bf16x8 {
-    return ldv(st, (2 * kb + j / DB) * DB + j % DB);
-  };
+  // state of the piece being computed
+  AttnItem it = piece(p_first);
+  int lim = 0;       // last key this lane's column may see
+  int min_lim = 0;   // smallest such limit in the workgroup: units entirely below it need no mask
 
   // probabilities 2p, 2p+1 of the unit in s[cur]: exp2, round to bf16, add to the
   // row sum (the sum uses the rounded values, like the numerator does)
@@ -330,8 +412,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     pf[cur].h[pr] = pk;
   };
 
+  // Body of unit u.  BC = position of the unit in the LDS ring (stage, key half),
+  // a compile-time value, so that every fragment read has an immediate offset.
   auto unit_body = [&](auto BC, int u) __attribute__((always_inline)) {
-    constexpr int b = decltype(BC)::value;                     // u mod 8
+    constexpr int b = decltype(BC)::value;
     constexpr int st_c = b / 2, kb_c = b % 2;                   // unit u
     constexpr int st_n = ((b + 1) % 8) / 2, kb_n = (b + 1) % 2; // unit u+1
     constexpr int st_nn = ((b + 2) % 8) / 2, kb_nn = b % 2;     // unit u+2
@@ -359,9 +443,11 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 #pragma unroll
     for (int i = 0; i < QS; ++i) {
       s[nxt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[nxt], 0, 0, 0);
-      ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk_u(st_n, kb_n, i + KDEPTH) : ldk_u(st_nn, kb_nn, i + KDEPTH - QS);
+      ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk(st_n * TILE_BYTES, kb_n, i + KDEPTH)
+                                         : ldk(st_nn * TILE_BYTES, kb_nn, i + KDEPTH - QS);
       o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[nxt].v[i / DB], o[i % DB], 0, 0, 0);
-      vf[i % VDEPTH] = (i + VDEPTH < PS) ? ldv_u(st_p, kb_p, i + VDEPTH) : ldv_u(st_c, kb_c, i + VDEPTH - PS);
+      vf[i % VDEPTH] = (i + VDEPTH < PS) ? ldv(st_p * TILE_BYTES, kb_p, i + VDEPTH)
+                                         : ldv(st_c * TILE_BYTES, kb_c, i + VDEPTH - PS);
 #pragma unroll
       for (int jj = 0; jj < PPS; ++jj) exp_pair(cur, i * PPS + jj);
       // within the step: an MFMA, the K fragment read, half of the vector work, the
@@ -379,6 +465,14 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     // sinks it below the branch that follows, away from the MFMAs it should hide under
     asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(rs));
     __builtin_amdgcn_sched_barrier(0);
+    if (u == 0) {
+      // the O^T MFMAs of a piece's first body belong to no unit (zero probabilities
+      // times whatever the ring stage held): the accumulation starts here
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    }
     if (__any(rs > kRowSumLimit)) {
       // Some column saw a score far above its reference (or has no reference yet):
       // take the unit's true maximum (one query column per lane, its key halves in
@@ -409,120 +503,162 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     l_run += rs;
   };
 
-  // ---- prologue: tiles 0 and 1 on their way, stage 3 cleared ------------------------
-  issue_tile(0, 0);
-  if (nt > 1) issue_tile(1, 1);
-  {
-    // the first unit's body multiplies V^T fragments of "unit -1" (stage 3) by zero
-    // probabilities; clear that stage so that no stale NaN pattern can leak in
-    const u32x4 z = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int i = 0; i < TILE_BYTES / 16 / NT; ++i) *(u32x4*)(&sv[3][(tid + NT * i) * 16]) = z;
-  }
-  // Everything issued so far (the Q fragments included) must have landed before the
-  // loop; a wait left to the compiler would sit inside the loop, where it would
-  // also cover the loads of later tiles.
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-  wg_barrier();
-
-  // S^T of unit 0 on its own, then the operand buffers as the first body expects them
-#pragma unroll
-  for (int j = 0; j < KDEPTH; ++j) ka[j] = ldk_u(0, 0, j);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s[0][r] = 0.f;
-#pragma unroll
-  for (int i = 0; i < QS; ++i) {
-    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[0], 0, 0, 0);
-    ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk_u(0, 0, i + KDEPTH) : ldk_u(0, 1, i + KDEPTH - QS);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-#pragma unroll
-  for (int j = 0; j < VDEPTH; ++j) vf[j] = ldv_u(3, 1, j);   // "unit -1": cleared stage
-  {
-    const bf16x2 z2 = {(__bf16)0.0f, (__bf16)0.0f};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) pf[1].h[j] = z2;
-  }
-
-  // iteration t = units 2t and 2t+1; tile t+2 is requested at its start and awaited
-  // at its end, before the barrier after which the next iteration starts reading it
+  // iteration = one tile = units 2t and 2t+1 of the piece (U units in all); TC is
+  // the tile's ring stage.  The tile two places down the stream is requested at
+  // its start and awaited at its end, before the barrier after which the next
+  // iteration starts reading the tile in between.
+  int U = 0;
   auto iteration = [&](auto TC, int t) __attribute__((always_inline)) {
-    constexpr int ts = decltype(TC)::value;   // t mod 4
-    if (t + 2 < nt) issue_tile((ts + 2) % NSTAGE, t + 2);
+    constexpr int ts = decltype(TC)::value;
+    issue_next((ts + 2) % NSTAGE);
     unit_body(std::integral_constant<int, 2 * ts>{}, 2 * t);
     if (2 * t + 1 < U) unit_body(std::integral_constant<int, 2 * ts + 1>{}, 2 * t + 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t+2 is in LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the requested tile is in LDS
     wg_barrier();
   };
-  for (int t = 0; t < nt; t += 4) {
-    iteration(std::integral_constant<int, 0>{}, t);
-    if (t + 1 < nt) iteration(std::integral_constant<int, 1>{}, t + 1);
-    if (t + 2 < nt) iteration(std::integral_constant<int, 2>{}, t + 2);
-    if (t + 3 < nt) iteration(std::integral_constant<int, 3>{}, t + 3);
-  }
 
-  // ---- drain: O^T += V^T P^T of the last unit ------------------------------------------
-  {
-    const int ul = U - 1;
-    const int st = (ul >> 1) & 3, kb = ul & 1;
-    const unsigned char* vbase_l = SV(st) + 2 * kb * 16 * ROWB;
-    auto ldv_l = [&](int j) __attribute__((always_inline)) -> bf16x8 {
-      const unsigned char* vp = vbase_l + (j / DB) * 16 * ROWB + voff[j % DB];
-      union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
-      cat.h.a = lds_read_tr16(vp);
-      cat.h.b = lds_read_tr16(vp + 8 * ROWB);
-      return cat.v;
-    };
-    // the fragments preloaded by the last body belong to this unit already
-    if (ul & 1) {
+  // ---- start-up: Q of the first piece, the first two tiles of the stream ------------
+  q_request(it);
+  issue_next(0);
+  issue_next(1);
+  q_collect(2);
+  // Everything issued so far must have landed before the loop; a wait left to the
+  // compiler would sit inside the loop, where it would also cover later tiles.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  wg_barrier();
+
+  int ph = 0;   // ring stage of the current piece's first tile
+  for (int p = p_first;;) {
+    const int tokc = min(tok, it.n_tok - 1);
+    lim = min(it.pos0 + tokc, it.k_end - 1);
+    min_lim = min(it.pos0, it.k_end - 1);
+    const int nkeys = it.k_end - it.k_begin;
+    const int nt = (nkeys + BN - 1) / BN;
+    U = (nkeys + 31) / 32;
+    m_run = -1e30f;
+    l_run = 0.f;
+    mc = m_run * c;
+
+    // S^T of unit 0 on its own, then the operand buffers as the first body expects
+    // them.  The ring stage is a run-time value here (and only here and in the drain).
+    {
+      const int off0 = ph * TILE_BYTES;
+      const int offm = ((ph + 3) & 3) * TILE_BYTES;   // "unit -1": any stage, see unit_body
 #pragma unroll
-      for (int i = 0; i < PS; ++i) {
-        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[1].v[i / DB], o[i % DB], 0, 0, 0);
-        if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv_l(i + VDEPTH);
+      for (int j = 0; j < KDEPTH; ++j) ka[j] = ldk(off0, 0, j);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[0][r] = 0.f;
+      // ring position of unit 0 is 2*ph: s[] and pf[] are indexed by its parity, 0
+#pragma unroll
+      for (int i = 0; i < QS; ++i) {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[0], 0, 0, 0);
+        ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk(off0, 0, i + KDEPTH) : ldk(off0, 1, i + KDEPTH - QS);
+        __builtin_amdgcn_sched_barrier(0);
       }
-    } else {
 #pragma unroll
-      for (int i = 0; i < PS; ++i) {
-        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[0].v[i / DB], o[i % DB], 0, 0, 0);
-        if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv_l(i + VDEPTH);
+      for (int j = 0; j < VDEPTH; ++j) vf[j] = ldv(offm, 1, j);
+      const bf16x2 z2 = {(__bf16)0.0f, (__bf16)0.0f};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pf[1].h[j] = z2;
+    }
+
+    // tiles of the piece, the loop unrolled over the four ring stages
+    const int tau1 = ph + nt;
+    for (int tb = 0; tb < tau1; tb += 4) {
+      if (tb >= ph) iteration(std::integral_constant<int, 0>{}, tb - ph);
+      if (tb + 1 >= ph && tb + 1 < tau1) iteration(std::integral_constant<int, 1>{}, tb + 1 - ph);
+      if (tb + 2 >= ph && tb + 2 < tau1) iteration(std::integral_constant<int, 2>{}, tb + 2 - ph);
+      if (tb + 3 >= ph && tb + 3 < tau1) iteration(std::integral_constant<int, 3>{}, tb + 3 - ph);
+    }
+
+    // request the next piece's Q rows; they are collected after the epilogue
+    const AttnItem done = it;
+    const bool more = p + 1 < p_last;
+    if (more) {
+      it = piece(p + 1);
+      q_request(it);
+    } else {
+      // (defined on every path, so that the values are not kept alive across the key loop)
+#pragma unroll
+      for (int k = 0; k < 2 * IPW; ++k) qraw[0][k] = qraw[1][k] = u32x4{0u, 0u, 0u, 0u};
+    }
+    const int st_area = (ph + nt + 2) & 3;   // the stage the next tile request goes to
+
+    // ---- drain: O^T += V^T P^T of the last unit ----------------------------------------
+    {
+      const int ul = U - 1;
+      const int off = (((ul >> 1) + ph) & 3) * TILE_BYTES;
+      const int kb = ul & 1;
+      // the fragments preloaded by the last body belong to this unit already
+      if (ul & 1) {
+#pragma unroll
+        for (int i = 0; i < PS; ++i) {
+          o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[1].v[i / DB], o[i % DB], 0, 0, 0);
+          if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < PS; ++i) {
+          o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[0].v[i / DB], o[i % DB], 0, 0, 0);
+          if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
+        }
       }
     }
-  }
 
-  // ---- epilogue ---------------------------------------------------------------------
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (it.part < 0) {
-    if (valid) {
+    // ---- epilogue ---------------------------------------------------------------------
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (done.part < 0) {
+      // final rows, turned around in the wave's staging area
       const float inv = 1.0f / l_tot;
-      uint16_t* op = P.out + qoff;
+      const uint32_t wbase = carea_of(st_area) + (uint32_t)hi * 8u;
+      int grow[2 * IPW];                // head-row (token * Hq + head) of the row in out, -1: not a row of this tile
+#pragma unroll
+      for (int k = 0; k < 2 * IPW; ++k) {
+        int hk, tk;
+        row_of(k, &hk, &tk);
+        grow[k] = (hk < G && tk < done.n_tok) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int dbl = 0; dbl < DB / 2; ++dbl)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[h * (DB / 2) + dbl][4 * b + e] * inv);
+            *(__attribute__((address_space(3))) bf16x4*)(lds_ptr)(uintptr_t)(wbase + ((uint32_t)((dbl * 4 + b) * 16) ^ cx)) = w;
+          }
+#pragma unroll
+        for (int k = 0; k < 2 * IPW; ++k) {
+          const u32x4 val = *(const __attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(
+              area_of(st_area, k) + roff);
+          if (grow[k] >= 0) *(u32x4*)(P.out + (int64_t)grow[k] * D + (lane % NS) * 8 + h * (D / 2)) = val;
+        }
+      }
+    } else {
+      const int64_t slot = ((int64_t)done.part * Hkv + kvh) * kTileRows + r_tile;
+      float* po = P.part_o + slot * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          bf16x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][4 * b + e] * inv);
-          *(bf16x4*)(op + db * 32 + 8 * b + 4 * hi) = w;
+          float4 w;
+          w.x = o[db][4 * b + 0];
+          w.y = o[db][4 * b + 1];
+          w.z = o[db][4 * b + 2];
+          w.w = o[db][4 * b + 3];
+          *(float4*)(po + db * 32 + 8 * b + 4 * hi) = w;
         }
-    }
-  } else {
-    const int64_t slot = ((int64_t)it.part * Hkv + kvh) * kTileRows + r_tile;
-    float* po = P.part_o + slot * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        float4 w;
-        w.x = o[db][4 * b + 0];
-        w.y = o[db][4 * b + 1];
-        w.z = o[db][4 * b + 2];
-        w.w = o[db][4 * b + 3];
-        *(float4*)(po + db * 32 + 8 * b + 4 * hi) = w;
+      if (hi == 0) {
+        P.part_ml[slot * 2 + 0] = m_run;
+        P.part_ml[slot * 2 + 1] = l_tot;
       }
-    if (hi == 0) {
-      P.part_ml[slot * 2 + 0] = m_run;
-      P.part_ml[slot * 2 + 1] = l_tot;
     }
+    if (!more) break;
+    q_collect(st_area);
+    ++p;
+    ph = (ph + nt) & 3;
   }
 }
 
@@ -655,35 +791,34 @@ int profile_read(double ms[3], int32_t launches[3]) {
 }
 
 int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
-                     float* part_o, float* part_ml, const AttnItem* items, int n_items, void* stream) {
+                     float* part_o, float* part_ml, const AttnItem* items, int n_items,
+                     const uint16_t* first, int n_queues, void* stream) {
   hipStream_t st = (hipStream_t)stream;
-  for (int base = 0; base < n_items; base += kMaxAttnItems) {
-    AttnParams P;
-    P.q = (const uint16_t*)q;
-    P.k = (const uint16_t*)k;
-    P.v = (const uint16_t*)v;
-    P.out = (uint16_t*)out;
-    P.part_o = part_o;
-    P.part_ml = part_ml;
-    P.Hq = ls.Hq;
-    P.Hkv = ls.Hkv;
-    P.G = ls.G;
-    P.TM = ls.TM;
-    P.c = ls.c;
-    const int n = n_items - base < kMaxAttnItems ? n_items - base : kMaxAttnItems;
-    P.n_items = n;
-    for (int i = 0; i < n; ++i) P.items[i] = items[base + i];
-    dim3 grid((unsigned)(n * ls.Hkv));
-    prof_begin(0, st);
-    if (ls.D == 128)
-      hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(512), 0, st, P);
-    else
-      hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(512), 0, st, P);
-    prof_end(st);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
-  }
-  return 0;
+  if (n_items <= 0 || n_queues <= 0) return 0;
+  if (n_items > kMaxAttnItems || n_queues > kMaxQueues) return (int)hipErrorInvalidValue;
+  AttnParams P;
+  P.q = (const uint16_t*)q;
+  P.k = (const uint16_t*)k;
+  P.v = (const uint16_t*)v;
+  P.out = (uint16_t*)out;
+  P.part_o = part_o;
+  P.part_ml = part_ml;
+  P.Hq = ls.Hq;
+  P.Hkv = ls.Hkv;
+  P.G = ls.G;
+  P.TM = ls.TM;
+  P.c = ls.c;
+  P.n_queues = n_queues;
+  for (int j = 0; j <= n_queues; ++j) P.first[j] = first[j];
+  for (int i = 0; i < n_items; ++i) P.items[i] = items[i];
+  dim3 grid((unsigned)(n_queues * ls.Hkv));
+  prof_begin(0, st);
+  if (ls.D == 128)
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(512), 0, st, P);
+  else
+    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(512), 0, st, P);
+  prof_end(st);
+  return (int)hipGetLastError();
 }
 
 int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,

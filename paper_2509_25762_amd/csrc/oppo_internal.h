@@ -7,7 +7,7 @@
 namespace oppo {
 
 // Rows of the packed (token x q-head-of-group) query tile one workgroup owns:
-// 4 waves x 64 query columns.
+// 8 waves x 32 query columns.
 constexpr int kTileRows = 256;
 // Keys per iteration of the key loop.
 constexpr int kKeyTile = 64;
@@ -15,13 +15,15 @@ constexpr int kKeyTile = 64;
 constexpr int kMaxSplit = 32;
 // Work descriptors travel by value in the kernel-argument segment, so the
 // host arrays are snapshotted at launch time without any staging copy.
-constexpr int kMaxAttnItems = 1000;     // 1000 * 32 B + header < 32 KiB
+constexpr int kMaxAttnItems = 960;      // 960 * 32 B + queue table + header < 32 KiB
+constexpr int kMaxQueues = 256;         // persistent workgroups per kv-head
 constexpr int kMaxCombineItems = 1000;  // 1000 * 16 B + header
 constexpr int kMaxAppendItems = 1000;   // 1000 * 16 B + header
 
-// One workgroup's share of the attention: a tile of up to TM tokens of one
-// sequence (all G q-heads of one kv-head; the kv-head comes from the block
-// index) against the key range [k_begin, k_end) of that sequence.
+// One piece of attention work: a tile of up to TM tokens of one sequence (all G
+// q-heads of one kv-head; the kv-head comes from the block index) against the
+// key range [k_begin, k_end) of that sequence.  A workgroup runs a queue of
+// pieces one after the other.
 struct AttnItem {
   int64_t kv_row0;  // row of the sequence's token 0 in the k/v arrays
   int32_t q_row0;   // row of the tile's first token in q/out
@@ -56,7 +58,8 @@ struct LayerShape {
 
 // Launchers (kernels.hip).  Return a hipError_t as int (0 = success).
 int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
-                     float* part_o, float* part_ml, const AttnItem* items, int n_items, void* stream);
+                     float* part_o, float* part_ml, const AttnItem* items, int n_items,
+                     const uint16_t* first, int n_queues, void* stream);
 int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,
                    const CombineItem* items, int n_items, void* stream);
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,

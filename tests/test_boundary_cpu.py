@@ -193,9 +193,13 @@ def test_planner_covers_every_key_exactly_once(lib):
             n_parts = _check_plan(desc, kvb, ql, items, 256 // 4)
             if split == 1:
                 assert n_parts == 0
-            # default order: longest key range first
-            lens = items[:, 5] - items[:, 4]
-            assert np.all(np.diff(lens) <= 0)
+            # pieces come grouped by queue; within a queue the longest key range (in 64-key tiles) first
+            queues = items[:, 7]
+            assert np.all(np.diff(queues) >= 0) and queues[0] == 0 and queues[-1] < 256 // 8
+            assert set(queues.tolist()) == set(range(int(queues[-1]) + 1))
+            for j in np.unique(queues):
+                lens = (items[:, 5] - items[:, 4])[queues == j]
+                assert np.all(np.diff(-(-lens // 64)) <= 0)
     ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)
     # without a workspace nothing is ever split
     items = ob.oppo_plan_debug(desc, [5000], [256], 0)
@@ -205,7 +209,11 @@ def test_planner_covers_every_key_exactly_once(lib):
 def test_planner_splits_a_thin_tail_but_not_a_full_batch(lib):
     desc = _desc()
     ws = ob.oppo_workspace_bytes(desc, 64, 1 << 16)
-    tail = ob.oppo_plan_debug(desc, [3000], [256], ws)             # one straggler: 32 workgroups unsplit
+    tail = ob.oppo_plan_debug(desc, [3000], [256], ws)             # one straggler: 4 query tiles for 32 queues
     assert len(tail) > 4 and np.all(tail[:, 6] >= 0)
-    full = ob.oppo_plan_debug(desc, np.full(64, 700), np.full(64, 256), ws)   # 2048 workgroups
+    assert len(set(tail[:, 7].tolist())) == 32                    # every queue gets a share ...
+    keys = np.bincount(tail[:, 7], weights=tail[:, 5] - tail[:, 4])
+    assert keys.max() - keys.min() <= 3 * 64                      # ... of about the same length
+    full = ob.oppo_plan_debug(desc, np.full(64, 700), np.full(64, 256), ws)   # 8 query tiles per queue
     assert np.all(full[:, 6] == -1) and len(full) == 256
+    assert np.all(np.bincount(full[:, 7]) == 8)
