@@ -127,6 +127,26 @@ int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cac
                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Steps 1 and 2 in one call and one kernel launch: appends the chunk's keys and
+ * values to the cache (exactly as oppo_kv_append would) and computes the
+ * chunk's attention rows (exactly as oppo_chunk_prefill_attn would afterwards:
+ * the same bits in out and in the cache).  For callers that have the chunk's
+ * q, k and v together, as a scoring model's layer does after its projections
+ * (Sec. 3.1): it saves a launch and a pass over k_new / v_new per layer and
+ * chunk.  cache->kv_len is the length BEFORE the chunk; on success
+ * kv_len[i] += q_len_i.  k_new, v_new: device bf16 [cu_q[B]][Hkv][D], rows as in
+ * q; the attention reads the chunk's own keys and values from them, and the
+ * kernel writes them to their cache slots, which nothing reads before the
+ * call's work has completed on the stream.
+ * Errors: those of the two calls; on any error nothing is enqueued and kv_len
+ * is unchanged.
+ */
+int oppo_chunk_step(const oppo_attn_desc* desc, oppo_kv_cache* cache,
+                    const int32_t* cu_q /* host [batch+1] */,
+                    const void* q, const void* k_new, const void* v_new, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One-shot causal prefill of whole sequences, without a cache: the reference
  * side of the streaming-equivalence invariant (Sec. 3.1, Eq. 3) on the device.
  * Sequence i owns rows [cu_seq[i], cu_seq[i+1]) of q/out (device bf16

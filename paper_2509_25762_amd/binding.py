@@ -29,7 +29,7 @@ OPT_ORDER = 1
 OPT_NUM_CUS = 2
 
 EXPORTS = [
-    "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_full_prefill_ref",
+    "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version",
     "oppo_profile_enable", "oppo_profile_read",
 ]
@@ -73,6 +73,9 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_prefill_attn.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp,
                                             vp, ctypes.c_size_t, vp]
     lib.oppo_chunk_prefill_attn.restype = ctypes.c_int
+    lib.oppo_chunk_step.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp, vp,
+                                    vp, ctypes.c_size_t, vp]
+    lib.oppo_chunk_step.restype = ctypes.c_int
     lib.oppo_full_prefill_ref.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, vp, vp, vp, vp, vp,
                                           ctypes.c_size_t, vp]
     lib.oppo_full_prefill_ref.restype = ctypes.c_int
@@ -205,6 +208,14 @@ def oppo_chunk_prefill_attn(desc: AttnDesc, cache: KVCache, cu_q, q, out, worksp
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().oppo_chunk_prefill_attn(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
                                           _dev_ptr(out), _dev_ptr(workspace), ws_bytes, _stream_ptr(stream)))
+
+
+def oppo_chunk_step(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, workspace=None, stream=None) -> None:
+    cu = _i32(cu_q, cache.batch + 1)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().oppo_chunk_step(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
+                                  _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out), _dev_ptr(workspace), ws_bytes,
+                                  _stream_ptr(stream)))
 
 
 def oppo_full_prefill_ref(desc: AttnDesc, cu_seq, q, k, v, out, workspace=None, stream=None) -> None:

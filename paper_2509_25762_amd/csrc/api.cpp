@@ -252,7 +252,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     oppo::AttnItem it;
     it.kv_row0 = s.kv_row0;
     it.q_row0 = s.q_row0 + qt.j0;
-    it.n_tok = qt.n_tok;
+    it.n_tok = oppo::pack_tokens(qt.n_tok, qt.j0 / ls.TM);
     it.pos0 = s.kv_before + qt.j0;
     it.k_begin = pc.t0 * oppo::kKeyTile;
     it.k_end = std::min<int32_t>(qt.keys, pc.t1 * oppo::kKeyTile);
@@ -297,8 +297,11 @@ void make_plans(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, si
   }
 }
 
-int run_attention(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, const void* q, const void* k,
-                  const void* v, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+// k_new / v_new non-null: the appending variant (the chunk's keys and values are
+// read from there and written into k / v by the same kernel).
+int run_attention(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, const void* q, void* k, void* v,
+                  const void* k_new, const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                  void* stream) {
   size_t slots = 0;
   float* part_o = nullptr;
   float* part_ml = nullptr;
@@ -308,11 +311,14 @@ int run_attention(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, 
     part_o = (float*)workspace;
     part_ml = part_o + slots * (size_t)ls.Hkv * oppo::kTileRows * (size_t)ls.D;
   }
+  for (const SeqView& s : seqs)
+    if (s.q_len / ls.TM >= (1 << 22))
+      return fail(OPPO_ERR_UNSUPPORTED, "%d rows of one sequence in one call exceed the work descriptor's range", s.q_len);
   std::vector<Plan> plans;
   make_plans(ls, seqs, slots, &plans);
   for (const Plan& plan : plans) {
-    const int e = oppo::launch_attention(ls, q, k, v, out, part_o, part_ml, plan.pieces.data(), (int)plan.pieces.size(),
-                                         plan.first.data(), (int)plan.first.size() - 1, stream);
+    const int e = oppo::launch_attention(ls, q, k, v, k_new, v_new, out, part_o, part_ml, plan.pieces.data(),
+                                         (int)plan.pieces.size(), plan.first.data(), (int)plan.first.size() - 1, stream);
     if (e) return fail(OPPO_ERR_HIP, "attention launch failed: %s", oppo::hip_error_string(e));
   }
   for (const Plan& plan : plans) {
@@ -444,7 +450,53 @@ int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cac
     return fail(OPPO_ERR_UNSUPPORTED, "%d query rows x %d heads exceed the 32-bit row index of the kernel", cu_q[B], ls.Hq);
   if (seqs.empty()) return OPPO_OK;
   if (!cache->k || !cache->v || !q || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
-  return run_attention(ls, seqs, q, cache->k, cache->v, out, workspace, workspace_bytes, stream);
+  return run_attention(ls, seqs, q, cache->k, cache->v, nullptr, nullptr, out, workspace, workspace_bytes, stream);
+}
+
+int oppo_chunk_step(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q, const void* q,
+                    const void* k_new, const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  if (!cache) return fail(OPPO_ERR_INVALID, "cache is null");
+  if (cache->batch < 0) return fail(OPPO_ERR_INVALID, "cache->batch is negative");
+  if (!cache->slot_begin || !cache->kv_len) return fail(OPPO_ERR_INVALID, "cache length arrays are null");
+  const int32_t B = cache->batch;
+  rc = check_cu(cu_q, B, "cu_q");
+  if (rc) return rc;
+  if (cache->slot_begin[0] < 0) return fail(OPPO_ERR_INVALID, "slot_begin[0] is negative");
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t cap = cache->slot_begin[i + 1] - cache->slot_begin[i];
+    if (cap < 0) return fail(OPPO_ERR_INVALID, "slot_begin decreases at %d", i);
+    if (cache->kv_len[i] < 0 || cache->kv_len[i] > cap)
+      return fail(OPPO_ERR_INVALID, "kv_len[%d]=%d outside its slab of %lld slots", i, cache->kv_len[i], (long long)cap);
+  }
+  std::vector<SeqView> seqs;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t cap = cache->slot_begin[i + 1] - cache->slot_begin[i];
+    const int32_t ql = cu_q[i + 1] - cu_q[i];
+    if ((int64_t)cache->kv_len[i] + ql > cap)
+      return fail(OPPO_ERR_CAPACITY, "sequence %d: %d cached + %d new tokens exceed %lld slots", i, cache->kv_len[i], ql,
+                  (long long)cap);
+    if (ql == 0) continue;
+    SeqView s;
+    s.kv_row0 = cache->slot_begin[i];
+    s.q_row0 = cu_q[i];
+    s.q_len = ql;
+    s.kv_before = cache->kv_len[i];
+    seqs.push_back(s);
+  }
+  rc = check_workspace(ls, workspace, workspace_bytes);
+  if (rc) return rc;
+  if ((int64_t)cu_q[B] * ls.Hq > INT32_MAX)
+    return fail(OPPO_ERR_UNSUPPORTED, "%d query rows x %d heads exceed the 32-bit row index of the kernel", cu_q[B], ls.Hq);
+  if (seqs.empty()) return OPPO_OK;
+  if (!cache->k || !cache->v || !q || !k_new || !v_new || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
+  rc = run_attention(ls, seqs, q, cache->k, cache->v, k_new, v_new, out, workspace, workspace_bytes, stream);
+  if (rc) return rc;
+  for (int32_t i = 0; i < B; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
+  return OPPO_OK;
 }
 
 int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B, const int32_t* cu_seq, const void* q, const void* k,
@@ -472,7 +524,8 @@ int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B, const int32_t* 
   }
   if (seqs.empty()) return OPPO_OK;
   if (!q || !k || !v || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
-  return run_attention(ls, seqs, q, k, v, out, workspace, workspace_bytes, stream);
+  return run_attention(ls, seqs, q, const_cast<void*>(k), const_cast<void*>(v), nullptr, nullptr, out, workspace,
+                       workspace_bytes, stream);
 }
 
 size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32_t max_q_tokens) {
@@ -534,7 +587,7 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
         int32_t* o = items + 8 * w;
         o[0] = (int32_t)it.kv_row0;
         o[1] = it.q_row0;
-        o[2] = it.n_tok;
+        o[2] = oppo::tokens_of(it);
         o[3] = it.pos0;
         o[4] = it.k_begin;
         o[5] = it.k_end;

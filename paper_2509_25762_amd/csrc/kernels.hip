@@ -32,8 +32,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 struct AttnParams {
   const uint16_t* q;
-  const uint16_t* k;
-  const uint16_t* v;
+  uint16_t* k;             // keys / values: the cache, or the packed sequences of a one-shot prefill
+  uint16_t* v;
+  const uint16_t* k_new;   // appending variant only: the chunk's keys / values, rows indexed like q
+  const uint16_t* v_new;
   uint16_t* out;
   float* part_o;
   float* part_ml;
@@ -125,7 +127,11 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 // boundaries: the first two tiles of the next piece are requested during the last
 // two iterations of the current one, and the next piece's Q fragments are
 // requested as soon as the current piece's last S^T MFMA has been issued.
-template <int D>
+// APPEND: the chunk's own keys and values are not in the cache yet.  The key loop
+// takes them from k_new / v_new, and the piece that starts a query tile's key
+// range also copies the tile's token rows into the cache (nothing in this launch
+// reads those cache rows).
+template <int D, bool APPEND>
 __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = 512;            // threads
   constexpr int NG = D / 8;          // 16-byte granules per K/V row
@@ -188,9 +194,6 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   };
 
   // ---- this lane's query column (row of the packed (head, token) tile) --------------
-  const int r_tile = wave * 32 + l32;
-  const int hh = r_tile / TM;
-  const int tok = r_tile - hh * TM;
   bf16x8 qf[KK];
 
   // ---- cooperative K/V tile loads ------------------------------------------------
@@ -223,21 +226,33 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NS = RB / 16;       // 16-byte slots of a row per round
   constexpr int RPC = 1024 / RB;    // rows per 1 KiB chunk
   typedef __attribute__((address_space(3))) unsigned char* lds_ptr;
-  // row-piece side: lane handles slot lane % NS of row lane / NS of each chunk
-  const uint32_t roff = (uint32_t)((lane / NS) * RB + (((lane % NS) ^ ((lane / NS) & (NS - 1))) * 16));
-  // column side: the lane's row l32 lies in chunk l32 / RPC
-  const uint32_t coff = (uint32_t)(((l32 / RPC) % IPW) * 8192 + (l32 % RPC) * RB);
-  const uint32_t cx = (uint32_t)(l32 & (NS - 1)) * 16u;
+  // The lane-dependent offsets below are needed at piece boundaries only.  They are
+  // derived from a copy of the lane number that the optimiser cannot see through,
+  // so that it recomputes them there instead of keeping them in registers (which
+  // the key loop has none to spare) for the whole kernel.
+  auto lane_now = [&]() __attribute__((always_inline)) -> int {
+    int x = lane;
+    asm volatile("" : "+v"(x));
+    return x;
+  };
+  // row-piece side: lane ln handles slot ln % NS of row ln / NS of each chunk
+  auto roff_of = [&](int ln) __attribute__((always_inline)) -> uint32_t {
+    return (uint32_t)((ln / NS) * RB + (((ln % NS) ^ ((ln / NS) & (NS - 1))) * 16));
+  };
+  // column side: the row of lane ln, (ln & 31), lies in chunk (ln & 31) / RPC; cx_of = its swizzle
+  auto cx_of = [&](int ln) __attribute__((always_inline)) -> uint32_t { return (uint32_t)(ln & (NS - 1)) * 16u; };
   auto area_of = [&](int stage, int k) __attribute__((always_inline)) -> uint32_t {   // chunk k of the area in `stage`
     return ((k / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
            (uint32_t)((k % IPW) * 8192);
   };
-  auto carea_of = [&](int stage) __attribute__((always_inline)) -> uint32_t {   // chunk of the lane's own row
-    return (((l32 / RPC) / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows + coff;
+  auto carea_of = [&](int stage, int ln) __attribute__((always_inline)) -> uint32_t {   // the row of lane ln in its chunk
+    const int row = ln & 31;
+    return (((row / RPC) / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
+           (uint32_t)(((row / RPC) % IPW) * 8192 + (row % RPC) * RB);
   };
-  // rows wave*32 + k*RPC + lane/NS of the packed tile -> (q-head of the group, token)
-  auto row_of = [&](int k, int* hk, int* tk) __attribute__((always_inline)) {
-    const int R0 = wave * 32 + lane / NS;
+  // rows wave*32 + k*RPC + ln/NS of the packed tile -> (q-head of the group, token)
+  auto row_of = [&](int ln, int k, int* hk, int* tk) __attribute__((always_inline)) {
+    const int R0 = (int)(wave_rows >> 10) * 32 + ln / NS;   // (wave number as a scalar)
     const int hh0 = R0 / TM;
     int t = R0 - hh0 * TM + k * RPC, h = hh0;
     while (t >= TM) t -= TM, ++h;
@@ -246,19 +261,22 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   };
   u32x4 qraw[2][2 * IPW];   // Q row pieces on their way: [half of D][chunk]
   auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
+    const int ln = lane_now();
 #pragma unroll
     for (int k = 0; k < 2 * IPW; ++k) {
       int hk, tk;
-      row_of(k, &hk, &tk);
+      row_of(ln, k, &hk, &tk);
       // rows beyond the tile repeat a valid row; their columns are never stored
-      const uint16_t* qp = P.q + ((int64_t)(a.q_row0 + min(tk, a.n_tok - 1)) * Hq + kvh * G + min(hk, G - 1)) * D + (lane % NS) * 8;
+      const uint16_t* qp = P.q + ((int64_t)(a.q_row0 + min(tk, tokens_of(a) - 1)) * Hq + kvh * G + min(hk, G - 1)) * D + (ln % NS) * 8;
 #pragma unroll
       for (int h = 0; h < 2; ++h) qraw[h][k] = *(const u32x4*)(qp + h * (D / 2));
     }
   };
   auto q_collect = [&](int stage) __attribute__((always_inline)) {
-    const uint32_t cbase = carea_of(stage);
-    const uint32_t cxh = cx ^ ((uint32_t)hi * 16u);   // the lane's slots are 2*kl + hi, swizzled
+    const int ln = lane_now();
+    const uint32_t roff = roff_of(ln);
+    const uint32_t cbase = carea_of(stage, ln);
+    const uint32_t cxh = cx_of(ln) ^ ((uint32_t)(ln >> 5) * 16u);   // the lane's slots are 2*kl + hi, swizzled
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -274,33 +292,73 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // p_first, then of the next piece, ...): all of it is wave-uniform.
   int c_piece = p_first;        // piece of the next tile to request
   int c_left = 0;               // keys of that piece not requested yet
-  const uint16_t* c_k = nullptr;  // first row of the next tile, this kv-head
-  const uint16_t* c_v = nullptr;
+  int c_cached = 0;             // APPEND: how many of them (counted from the next tile on) are in the cache
+  // first row of the next tile, this kv-head, as a byte address in k, and (APPEND) where
+  // that row would be in k_new; the v addresses are a fixed distance away
+  uintptr_t c_k = 0, c_kn = 0;
+  const uintptr_t k_to_v = (uintptr_t)P.v - (uintptr_t)P.k;
+  const uintptr_t kn_to_vn = APPEND ? (uintptr_t)P.v_new - (uintptr_t)P.k_new : 0;
+  const uintptr_t tile_step = (uintptr_t)BN * row_stride * 2u;
   auto cursor_open = [&]() __attribute__((always_inline)) {
     const AttnItem a = piece(c_piece);
-    const int64_t e = (((int64_t)a.kv_row0 + a.k_begin) * Hkv + kvh) * D;
-    c_k = P.k + e;
-    c_v = P.v + e;
+    c_k = (uintptr_t)(P.k + (((int64_t)a.kv_row0 + a.k_begin) * Hkv + kvh) * D);
     c_left = a.k_end - a.k_begin;
+    if (APPEND) {
+      const int j0 = tile_of(a) * TM;          // the tile's first token within its chunk
+      c_cached = (a.pos0 - j0) - a.k_begin;    // keys before the chunk are cached
+      c_kn = (uintptr_t)(P.k_new + (((int64_t)(a.q_row0 - j0) - c_cached) * Hkv + kvh) * D);
+    }
   };
   cursor_open();
   auto issue_next = [&](int stage) __attribute__((always_inline)) {
     if (c_piece >= p_last) return;
     const int last = c_left - 1;
+    // (LDS addresses are formed here from a copy of the wave's offset that the optimiser
+    // cannot see through: otherwise it keeps one precomputed address per stage, array and
+    // load in scalar registers for the whole kernel, and those run out)
+    uint32_t wave_rows_now = wave_rows;
+    asm volatile("" : "+s"(wave_rows_now));
+    if (APPEND && c_cached > 0 && c_cached < BN && c_cached <= last) {
+      // cache rows, then chunk rows: each lane's 16 bytes land at the LDS address of its
+      // lane number, so the two sources fill one tile with complementary lane masks
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      uint32_t ok = goffk[i], ov = goffv[i];
-      if (last < BN - 1) {  // ragged last tile: rows past the range repeat the last key
+      for (int i = 0; i < IPW; ++i) {
         const int r = (wave + 8 * i) * RPI + lrow;
-        const int rc = min(r, last);
-        ok = (uint32_t)(rc * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
-        ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
+        const int rc = min(r, last);   // rows past the range repeat the last key
+        const uint32_t ok = (uint32_t)(rc * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
+        const uint32_t ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
+        const uint32_t lk = lds_addr_of(&sk[stage][0]) + wave_rows_now + i * 8192u;
+        const uint32_t lv = lds_addr_of(&sv[stage][0]) + wave_rows_now + i * 8192u;
+        if (rc < c_cached) {
+          async_copy16((const void*)c_k, ok, lk);
+          async_copy16((const void*)(c_k + k_to_v), ov, lv);
+        } else {
+          async_copy16((const void*)c_kn, ok, lk);
+          async_copy16((const void*)(c_kn + kn_to_vn), ov, lv);
+        }
       }
-      async_copy16(c_k, ok, lds_addr_of(&sk[stage][0]) + wave_rows + i * 8192u);
-      async_copy16(c_v, ov, lds_addr_of(&sv[stage][0]) + wave_rows + i * 8192u);
+    } else {
+      const bool all_new = APPEND && c_cached <= 0;
+      const uintptr_t bk = all_new ? c_kn : c_k;
+      const uintptr_t bv = bk + (all_new ? kn_to_vn : k_to_v);
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        uint32_t ok = goffk[i], ov = goffv[i];
+        if (last < BN - 1) {  // ragged last tile: rows past the range repeat the last key
+          const int r = (wave + 8 * i) * RPI + lrow;
+          const int rc = min(r, last);
+          ok = (uint32_t)(rc * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
+          ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
+        }
+        async_copy16((const void*)bk, ok, lds_addr_of(&sk[stage][0]) + wave_rows_now + i * 8192u);
+        async_copy16((const void*)bv, ov, lds_addr_of(&sv[stage][0]) + wave_rows_now + i * 8192u);
+      }
     }
-    c_k += (int64_t)BN * row_stride;
-    c_v += (int64_t)BN * row_stride;
+    c_k += tile_step;
+    if (APPEND) {
+      c_kn += tile_step;
+      c_cached -= BN;
+    }
     c_left -= BN;
     if (c_left <= 0) {
       ++c_piece;
@@ -386,7 +444,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   // state of the piece being computed
   AttnItem it = piece(p_first);
-  int lim = 0;       // last key this lane's column may see
+  int lim = 0;       // last key this lane's column may see, minus 4 * (lane / 32): compared with the key
+                     // of the lane's register r of the other 32-lane half, see the mask in unit_body
   int min_lim = 0;   // smallest such limit in the workgroup: units entirely below it need no mask
 
   // probabilities 2p, 2p+1 of the unit in s[cur]: exp2, round to bf16, add to the
@@ -427,8 +486,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     if (key0 + 31 > min_lim) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = key0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-        if (key > lim) s[cur][r] = -INFINITY;
+        // register r holds key key0 + 8 * (r / 4) + 4 * (lane / 32) + r % 4
+        if (key0 + 8 * (r >> 2) + (r & 3) > lim) s[cur][r] = -INFINITY;
       }
     }
     // The probabilities of this unit are formed against the reference value m_run
@@ -529,15 +588,28 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   int ph = 0;   // ring stage of the current piece's first tile
   for (int p = p_first;;) {
-    const int tokc = min(tok, it.n_tok - 1);
-    lim = min(it.pos0 + tokc, it.k_end - 1);
+    // (per-lane values that only matter here are recomputed from an opaque copy of the
+    // lane number, see lane_now)
+    const int ln_top = lane_now();
+    const int r_tile = (int)(wave_rows >> 10) * 32 + (ln_top & 31);   // the lane's row of the packed tile
+    const int tok = r_tile % TM;                                      // its token within the tile
+    const int tokc = min(tok, tokens_of(it) - 1);
+    lim = min(it.pos0 + tokc, it.k_end - 1) - 4 * (ln_top >> 5);
     min_lim = min(it.pos0, it.k_end - 1);
     const int nkeys = it.k_end - it.k_begin;
     const int nt = (nkeys + BN - 1) / BN;
     U = (nkeys + 31) / 32;
     m_run = -1e30f;
     l_run = 0.f;
-    mc = m_run * c;
+    {
+      float c_now = c;
+      asm volatile("" : "+s"(c_now));
+      mc = m_run * c_now;
+    }
+    // the accumulators start undefined (they are cleared after the first body, see
+    // unit_body); saying so ends their live range at the previous piece's epilogue
+#pragma unroll
+    for (int db = 0; db < DB; ++db) asm volatile("" : "=v"(o[db]));
 
     // S^T of unit 0 on its own, then the operand buffers as the first body expects
     // them.  The ring stage is a run-time value here (and only here and in the drain).
@@ -584,24 +656,59 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     }
     const int st_area = (ph + nt + 2) & 3;   // the stage the next tile request goes to
 
+    // APPEND: the piece that starts the tile's key range moves the tile's token rows
+    // (this kv-head's D elements of each) from k_new / v_new into the cache, 16 bytes
+    // per thread and pass of CP_ROWS rows.  The first two passes are requested here
+    // and stored after the epilogue; query tiles of more than 2 * CP_ROWS tokens
+    // finish in a plain loop.  The data waits in the registers of s[1], which the
+    // key loop no longer needs and the next piece's first body clears.
+    constexpr int CP_ROWS = NT / NG;   // token rows per pass
+    const bool cp_on = APPEND && done.k_begin == 0;
+    const int cp_tid = (int)(wave_rows >> 4) + lane_now();   // thread number, recomputed here
+    const int cp_row = cp_tid / NG, cp_g = cp_tid % NG;
+    auto cp_src = [&](int row) __attribute__((always_inline)) -> int64_t {
+      return (((int64_t)done.q_row0 + row) * Hkv + kvh) * D + cp_g * 8;
+    };
+    auto cp_dst = [&](int row) __attribute__((always_inline)) -> int64_t {
+      return (((int64_t)done.kv_row0 + done.pos0 + row) * Hkv + kvh) * D + cp_g * 8;
+    };
+    auto park = [&](int slot, const u32x4& x) __attribute__((always_inline)) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[1][4 * slot + e] = __uint_as_float(x[e]);
+    };
+    auto unpark = [&](int slot) __attribute__((always_inline)) -> u32x4 {
+      u32x4 x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = __float_as_uint(s[1][4 * slot + e]);
+      return x;
+    };
+    if (cp_on) {
+#pragma unroll
+      for (int ps = 0; ps < 2; ++ps) {
+        const int row = ps * CP_ROWS + cp_row;
+        if (row < tokens_of(done)) {
+          park(2 * ps, *(const u32x4*)(P.k_new + cp_src(row)));
+          park(2 * ps + 1, *(const u32x4*)(P.v_new + cp_src(row)));
+        }
+      }
+    }
+
     // ---- drain: O^T += V^T P^T of the last unit ----------------------------------------
     {
       const int ul = U - 1;
       const int off = (((ul >> 1) + ph) & 3) * TILE_BYTES;
       const int kb = ul & 1;
-      // the fragments preloaded by the last body belong to this unit already
-      if (ul & 1) {
+      // the fragments preloaded by the last body belong to this unit already; its
+      // probabilities are pf[ul & 1] (picked as values: an array indexed at run time
+      // would be put into scratch memory)
+      bf16x8 e0 = pf[0].v[0], e1 = pf[0].v[1], d0 = pf[1].v[0], d1 = pf[1].v[1];
+      asm volatile("" : "+v"(e0), "+v"(e1), "+v"(d0), "+v"(d1));
+      const bool odd = (ul & 1) != 0;
+      const bf16x8 pl[2] = {odd ? d0 : e0, odd ? d1 : e1};
 #pragma unroll
-        for (int i = 0; i < PS; ++i) {
-          o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[1].v[i / DB], o[i % DB], 0, 0, 0);
-          if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < PS; ++i) {
-          o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[0].v[i / DB], o[i % DB], 0, 0, 0);
-          if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
-        }
+      for (int i = 0; i < PS; ++i) {
+        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pl[i / DB], o[i % DB], 0, 0, 0);
+        if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
       }
     }
 
@@ -610,13 +717,15 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     if (done.part < 0) {
       // final rows, turned around in the wave's staging area
       const float inv = 1.0f / l_tot;
-      const uint32_t wbase = carea_of(st_area) + (uint32_t)hi * 8u;
+      const int ln = lane_now();
+      const uint32_t roff = roff_of(ln), cx = cx_of(ln);
+      const uint32_t wbase = carea_of(st_area, ln) + (uint32_t)(ln >> 5) * 8u;
       int grow[2 * IPW];                // head-row (token * Hq + head) of the row in out, -1: not a row of this tile
 #pragma unroll
       for (int k = 0; k < 2 * IPW; ++k) {
         int hk, tk;
-        row_of(k, &hk, &tk);
-        grow[k] = (hk < G && tk < done.n_tok) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
+        row_of(ln, k, &hk, &tk);
+        grow[k] = (hk < G && tk < tokens_of(done)) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
       }
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -633,11 +742,13 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
         for (int k = 0; k < 2 * IPW; ++k) {
           const u32x4 val = *(const __attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(
               area_of(st_area, k) + roff);
-          if (grow[k] >= 0) *(u32x4*)(P.out + (int64_t)grow[k] * D + (lane % NS) * 8 + h * (D / 2)) = val;
+          if (grow[k] >= 0) *(u32x4*)(P.out + (int64_t)grow[k] * D + (ln % NS) * 8 + h * (D / 2)) = val;
         }
       }
     } else {
-      const int64_t slot = ((int64_t)done.part * Hkv + kvh) * kTileRows + r_tile;
+      const int lnp = lane_now();
+      const int hip = lnp >> 5;
+      const int64_t slot = ((int64_t)done.part * Hkv + kvh) * kTileRows + (int)(wave_rows >> 10) * 32 + (lnp & 31);
       float* po = P.part_o + slot * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -648,15 +759,31 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
           w.y = o[db][4 * b + 1];
           w.z = o[db][4 * b + 2];
           w.w = o[db][4 * b + 3];
-          *(float4*)(po + db * 32 + 8 * b + 4 * hi) = w;
+          *(float4*)(po + db * 32 + 8 * b + 4 * hip) = w;
         }
-      if (hi == 0) {
+      if (hip == 0) {
         P.part_ml[slot * 2 + 0] = m_run;
         P.part_ml[slot * 2 + 1] = l_tot;
       }
     }
+    if (cp_on) {
+#pragma unroll
+      for (int ps = 0; ps < 2; ++ps) {
+        const int row = ps * CP_ROWS + cp_row;
+        if (row < tokens_of(done)) {
+          *(u32x4*)(P.k + cp_dst(row)) = unpark(2 * ps);
+          *(u32x4*)(P.v + cp_dst(row)) = unpark(2 * ps + 1);
+        }
+      }
+      for (int row = 2 * CP_ROWS + cp_row; row < tokens_of(done); row += CP_ROWS) {
+        const u32x4 a = *(const u32x4*)(P.k_new + cp_src(row));
+        const u32x4 b = *(const u32x4*)(P.v_new + cp_src(row));
+        *(u32x4*)(P.k + cp_dst(row)) = a;
+        *(u32x4*)(P.v + cp_dst(row)) = b;
+      }
+    }
+    if (more) q_collect(st_area);
     if (!more) break;
-    q_collect(st_area);
     ++p;
     ph = (ph + nt) & 3;
   }
@@ -790,16 +917,18 @@ int profile_read(double ms[3], int32_t launches[3]) {
   return rc;
 }
 
-int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
-                     float* part_o, float* part_ml, const AttnItem* items, int n_items,
+int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, const void* k_new, const void* v_new,
+                     void* out, float* part_o, float* part_ml, const AttnItem* items, int n_items,
                      const uint16_t* first, int n_queues, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   if (n_items <= 0 || n_queues <= 0) return 0;
   if (n_items > kMaxAttnItems || n_queues > kMaxQueues) return (int)hipErrorInvalidValue;
   AttnParams P;
   P.q = (const uint16_t*)q;
-  P.k = (const uint16_t*)k;
-  P.v = (const uint16_t*)v;
+  P.k = (uint16_t*)k;
+  P.v = (uint16_t*)v;
+  P.k_new = (const uint16_t*)k_new;
+  P.v_new = (const uint16_t*)v_new;
   P.out = (uint16_t*)out;
   P.part_o = part_o;
   P.part_ml = part_ml;
@@ -812,11 +941,15 @@ int launch_attention(const LayerShape& ls, const void* q, const void* k, const v
   for (int j = 0; j <= n_queues; ++j) P.first[j] = first[j];
   for (int i = 0; i < n_items; ++i) P.items[i] = items[i];
   dim3 grid((unsigned)(n_queues * ls.Hkv));
+  const bool append = k_new != nullptr;
   prof_begin(0, st);
-  if (ls.D == 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(512), 0, st, P);
-  else
-    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(512), 0, st, P);
+  if (ls.D == 128) {
+    if (append) hipLaunchKernelGGL((attn_fwd_kernel<128, true>), grid, dim3(512), 0, st, P);
+    else hipLaunchKernelGGL((attn_fwd_kernel<128, false>), grid, dim3(512), 0, st, P);
+  } else {
+    if (append) hipLaunchKernelGGL((attn_fwd_kernel<64, true>), grid, dim3(512), 0, st, P);
+    else hipLaunchKernelGGL((attn_fwd_kernel<64, false>), grid, dim3(512), 0, st, P);
+  }
   prof_end(st);
   return (int)hipGetLastError();
 }

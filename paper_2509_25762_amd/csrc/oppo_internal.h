@@ -27,13 +27,21 @@ constexpr int kMaxAppendItems = 1000;   // 1000 * 16 B + header
 struct AttnItem {
   int64_t kv_row0;  // row of the sequence's token 0 in the k/v arrays
   int32_t q_row0;   // row of the tile's first token in q/out
-  int32_t n_tok;    // tokens in the tile, 1..TM
+  int32_t n_tok;    // tokens in the tile (1..TM) | index of the tile within its chunk << 9
   int32_t pos0;     // absolute position of the tile's first token
   int32_t k_begin;  // first key of the range (multiple of kKeyTile)
   int32_t k_end;    // one past the last key, <= pos0 + n_tok
   int32_t part;     // -1: write final bf16 rows; >= 0: partial slot to fill
 };
 static_assert(sizeof(AttnItem) == 32, "AttnItem layout");
+#if defined(__HIPCC__)
+#define OPPO_HD __host__ __device__
+#else
+#define OPPO_HD
+#endif
+OPPO_HD inline int32_t pack_tokens(int n_tok, int tile) { return n_tok | (tile << 9); }
+OPPO_HD inline int tokens_of(const AttnItem& a) { return a.n_tok & 511; }
+OPPO_HD inline int tile_of(const AttnItem& a) { return a.n_tok >> 9; }
 
 // Merge of the partial results of one split tile.
 struct CombineItem {
@@ -57,8 +65,11 @@ struct LayerShape {
 };
 
 // Launchers (kernels.hip).  Return a hipError_t as int (0 = success).
-int launch_attention(const LayerShape& ls, const void* q, const void* k, const void* v, void* out,
-                     float* part_o, float* part_ml, const AttnItem* items, int n_items,
+// k_new / v_new null: keys and values come from k / v alone.  Otherwise the
+// kernel also appends: a sequence's keys from position pos0 - tile * TM on are
+// read from k_new / v_new (rows indexed like q) and copied into k / v.
+int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, const void* k_new, const void* v_new,
+                     void* out, float* part_o, float* part_ml, const AttnItem* items, int n_items,
                      const uint16_t* first, int n_queues, void* stream);
 int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,
                    const CombineItem* items, int n_items, void* stream);

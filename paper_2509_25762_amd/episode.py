@@ -82,14 +82,18 @@ class StreamedEpisode:
         """Rewinds the host lengths to the state before pass `first_step`."""
         self.cache.kv_len[:] = self.steps[first_step].kv_before if self.steps else 0
 
-    def run_step(self, t: int, stream=None) -> None:
+    def run_step(self, t: int, stream=None, fused: bool = True) -> None:
+        """One pass: the fused call, or append followed by attention (same results)."""
         s = self.steps[t]
-        ob.oppo_kv_append(self.desc, self.cache, s.cu_q, s.k, s.v, stream)
-        ob.oppo_chunk_prefill_attn(self.desc, self.cache, s.cu_q, s.q, s.out, self.workspace, stream)
+        if fused:
+            ob.oppo_chunk_step(self.desc, self.cache, s.cu_q, s.q, s.k, s.v, s.out, self.workspace, stream)
+        else:
+            ob.oppo_kv_append(self.desc, self.cache, s.cu_q, s.k, s.v, stream)
+            ob.oppo_chunk_prefill_attn(self.desc, self.cache, s.cu_q, s.q, s.out, self.workspace, stream)
 
-    def run(self, first_step: int = 0, stream=None) -> None:
+    def run(self, first_step: int = 0, stream=None, fused: bool = True) -> None:
         for t in range(first_step, len(self.steps)):
-            self.run_step(t, stream)
+            self.run_step(t, stream, fused)
 
     def scatter_outputs(self) -> torch.Tensor:
         """Outputs of all passes at their token rows (int16 bits [T, Hq, D])."""

@@ -135,6 +135,28 @@ def test_attention_validation(lib):
         ob.oppo_full_prefill_ref(desc, [0, 5, 3], 0x1, 0x2, 0x3, 0x4, stream=0)
 
 
+def test_chunk_step_validation_leaves_lengths_untouched(lib):
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 0])
+    cases = [([0, 3, 6], ob.OPPO_ERR_CAPACITY),      # 6 + 3 > 8
+             ([1, 3, 6], ob.OPPO_ERR_INVALID),       # cu_q[0] != 0
+             ([0, 3, 2], ob.OPPO_ERR_INVALID)]       # decreasing
+    for cu, code in cases:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_chunk_step(desc, cache, cu, 0x3000, 0x4000, 0x5000, 0x6000, stream=0)
+        assert e.value.code == code
+        assert cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:            # rows to do, but a null device pointer
+        ob.oppo_chunk_step(desc, cache, [0, 1, 2], 0x3000, None, 0x5000, 0x6000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID and cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:            # bad descriptor
+        ob.oppo_chunk_step(_desc(D=96), cache, [0, 1, 2], 0x3000, 0x4000, 0x5000, 0x6000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_UNSUPPORTED
+    # a pass in which nobody has rows is legal and needs no device at all
+    ob.oppo_chunk_step(desc, cache, [0, 0, 0], None, None, None, None, stream=0)
+    assert cache.kv_len.tolist() == [6, 0]
+
+
 def test_options_validation(lib):
     with pytest.raises(ob.OppoError):
         ob.oppo_set_option(99, 1)

@@ -91,6 +91,14 @@ def test_full_size_config(gpu, idx):
         assert torch.equal(se.cache_v[b:b + n], se.v_all[lo:hi]), f"V cache of sequence {i}"
         assert bool((se.cache_k[b + n:e] == -1).all()) and bool((se.cache_v[b + n:e] == -1).all())
 
+    # ---- fused call == append + attention, bit for bit ------------------------------
+    se2 = episode.StreamedEpisode(ep, chunks)
+    se2.run(fused=False)
+    torch.cuda.synchronize()
+    assert torch.equal(se2.scatter_outputs(), out_dev), "fused and two-call outputs differ"
+    assert torch.equal(se2.cache_k, se.cache_k) and torch.equal(se2.cache_v, se.cache_v)
+    del se2
+
     # ---- streamed == one-shot prefill on the device, all rows ----------------------
     full = se.full_prefill()
     torch.cuda.synchronize()

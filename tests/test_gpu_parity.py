@@ -74,14 +74,21 @@ def check_cache(se, ep, torch):
 
 
 def run_and_check(gpu, ep, chunks, ref=None, what=""):
+    """Streams the episode twice - with the fused call (oppo_chunk_step) and with
+    oppo_kv_append + oppo_chunk_prefill_attn - and checks both against the oracle;
+    the two must agree bit for bit, in the outputs and in the cache."""
     binding, episode, torch = gpu
-    se = episode.StreamedEpisode(ep, chunks)
-    se.run()
-    torch.cuda.synchronize()
-    out = se.scatter_outputs().cpu().numpy().view(np.uint16)
     ref = oracle_outputs(ep) if ref is None else ref
-    res = check_outputs(out, ref, what)
-    check_cache(se, ep, torch)
+    outs = []
+    for fused in (False, True):
+        se = episode.StreamedEpisode(ep, chunks)
+        se.run(fused=fused)
+        torch.cuda.synchronize()
+        out = se.scatter_outputs().cpu().numpy().view(np.uint16)
+        res = check_outputs(out, ref, f"{what} fused={fused}")
+        check_cache(se, ep, torch)
+        outs.append(out)
+    assert np.array_equal(outs[0], outs[1]), f"{what}: fused and two-call results differ"
     return se, out, res
 
 
