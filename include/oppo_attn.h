@@ -175,8 +175,8 @@ size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32
  *                       1 = never split, n >= 2 = cut every key range into up
  *                       to n pieces when a workspace is given.
  *   OPPO_OPT_ORDER    : order of the pieces within a workgroup's queue:
- *                       0 = longest first (default), 1 = input order,
- *                       2 = shortest first.
+ *                       0 = as scheduled (default: sequences with the most
+ *                       work first), 1 = input order, 2 = shortest first.
  *   OPPO_OPT_NUM_CUS  : compute units the planner fills (default 256); the
  *                       attention launch has num_cus / Hkv workgroups (queues)
  *                       per kv-head, at least 1 and at most 256.

@@ -26,7 +26,7 @@ int fail(int code, const char* fmt, ...) {
 
 struct Options {
   int split_kv = 0;   // 0 auto, 1 off, n>=2 forced
-  int order = 0;      // within a queue: 0 longest first, 1 input order, 2 shortest first
+  int order = 0;      // within a queue: 0 as scheduled, 1 input order, 2 shortest first
   int num_cus = 256;
 };
 Options g_opt;
@@ -106,9 +106,10 @@ struct QTile { int seq; int32_t j0, n_tok, keys, ntile; };
 // The kernel runs one persistent workgroup per (queue, kv-head); the planner
 // decides which pieces each queue runs.  Two ways of filling the queues are
 // priced with the cost model above and the cheaper one is taken:
-//   * whole tiles, longest first onto the least loaded queue - no partial
-//     results, but the longest tile bounds the makespan and with few tiles per
-//     queue the loads are uneven (the thin tail passes of a long-tailed batch);
+//   * whole tiles, sequence by sequence onto the least loaded group of queues (see
+//     gang_schedule) - no partial results, but the longest tile bounds the
+//     makespan and with few tiles per queue the loads are uneven (the thin tail
+//     passes of a long-tailed batch);
 //   * the tiles' key ranges laid end to end and cut into equal shares, one per
 //     queue: a tile that straddles a cut is split there (on a 64-key boundary)
 //     and its pieces are merged afterwards.  A cut that falls close to a tile
@@ -117,7 +118,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
                  size_t lo, size_t hi, size_t slots_avail, size_t* next_slot, Plan* plan) {
   const int Q = queue_count(ls);
   const size_t n = hi - lo;
-  struct Piece { int tile; int t0, t1; int queue; };   // tiles [t0, t1) of query tile `tile`
+  struct Piece { int tile; int t0, t1; int queue; int rank; };   // key tiles [t0, t1) of query tile `tile`; rank = order of scheduling
   auto price = [&](const std::vector<Piece>& pcs, int nq, size_t* n_partial) {
     std::vector<float> load((size_t)nq, 0.f);
     size_t np = 0;
@@ -131,23 +132,61 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     if (n_partial) *n_partial = np;
     return ms + (np ? kMergeTiles + kMergeTilesPerPiece * (float)np : 0.f);
   };
-  // longest first onto the least loaded queue
-  auto list_schedule = [&](std::vector<Piece>& pcs) {
-    std::vector<size_t> idx(pcs.size());
-    for (size_t i = 0; i < idx.size(); ++i) idx[i] = i;
-    std::stable_sort(idx.begin(), idx.end(), [&](size_t a, size_t b) {
-      return pcs[a].t1 - pcs[a].t0 > pcs[b].t1 - pcs[b].t0;
-    });
-    typedef std::pair<float, int> Load;
-    std::vector<Load> heap;
-    for (int j = 0; j < Q; ++j) heap.push_back(Load(0.f, j));
-    auto later = [](const Load& a, const Load& b) { return a.first > b.first || (a.first == b.first && a.second > b.second); };
-    std::make_heap(heap.begin(), heap.end(), later);
-    for (size_t i : idx) {
-      std::pop_heap(heap.begin(), heap.end(), later);
-      pcs[i].queue = heap.back().second;
-      heap.back().first += (float)(pcs[i].t1 - pcs[i].t0) + kPieceTiles;
-      std::push_heap(heap.begin(), heap.end(), later);
+  // Whole pieces onto queues.  The pieces of one sequence (its query tiles of this
+  // pass) read the same keys and values, and the workgroups of one kv-head share a
+  // level-2 cache: scheduled side by side - on neighbouring queues, at about the
+  // same time - they fetch every K/V tile from memory once instead of once per
+  // query tile.  (Memory traffic matters beyond its bandwidth here: the chip runs
+  // against its power limit, and traffic that is saved turns into clock rate.)
+  // So sequences are taken in order of decreasing work, each one's pieces go as a
+  // gang onto a group of consecutive queues - the group, among those starting at
+  // multiples of the group size, that ends up least loaded - longest piece onto
+  // the least loaded queue of the group, and every queue runs its pieces in the
+  // order they were scheduled.
+  auto gang_schedule = [&](std::vector<Piece>& pcs) {
+    std::vector<std::vector<size_t>> of_seq(seqs.size());
+    for (size_t a = 0; a < pcs.size(); ++a) of_seq[tiles[pcs[a].tile].seq].push_back(a);
+    std::vector<int> order;
+    std::vector<int64_t> work(seqs.size(), 0);
+    for (size_t i = 0; i < seqs.size(); ++i) {
+      for (size_t a : of_seq[i]) work[i] += pcs[a].t1 - pcs[a].t0;
+      if (!of_seq[i].empty()) order.push_back((int)i);
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work[a] > work[b]; });
+    std::vector<float> load((size_t)Q, 0.f);
+    int rank = 0;
+    std::vector<int> qs;
+    for (int sq : order) {
+      std::vector<size_t>& mem = of_seq[sq];
+      std::stable_sort(mem.begin(), mem.end(), [&](size_t a, size_t b) {
+        return pcs[a].t1 - pcs[a].t0 > pcs[b].t1 - pcs[b].t0;
+      });
+      for (size_t m0 = 0; m0 < mem.size(); m0 += (size_t)Q) {
+        const int g = (int)std::min<size_t>((size_t)Q, mem.size() - m0);
+        int step = 1;   // largest divisor of Q that does not exceed the gang
+        for (int d = 1; d <= g; ++d)
+          if (Q % d == 0) step = d;
+        float best = 0.f;
+        int best_start = -1;
+        for (int st = 0; st < Q; st += step) {
+          qs.clear();
+          for (int m = 0; m < g; ++m) qs.push_back((st + m) % Q);
+          std::sort(qs.begin(), qs.end(), [&](int a, int b) { return load[a] < load[b] || (load[a] == load[b] && a < b); });
+          float mx = 0.f;
+          for (int m = 0; m < g; ++m)
+            mx = std::max(mx, load[qs[m]] + (float)(pcs[mem[m0 + m]].t1 - pcs[mem[m0 + m]].t0));
+          if (best_start < 0 || mx < best) best = mx, best_start = st;
+        }
+        qs.clear();
+        for (int m = 0; m < g; ++m) qs.push_back((best_start + m) % Q);
+        std::sort(qs.begin(), qs.end(), [&](int a, int b) { return load[a] < load[b] || (load[a] == load[b] && a < b); });
+        for (int m = 0; m < g; ++m) {
+          Piece& pc = pcs[mem[m0 + m]];
+          pc.queue = qs[m];
+          pc.rank = rank++;
+          load[qs[m]] += (float)(pc.t1 - pc.t0) + kPieceTiles;
+        }
+      }
     }
   };
 
@@ -164,14 +203,14 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
       int t0 = 0;
       for (int p = 0; p < ns; ++p) {
         const int len = nt / ns + (p < nt % ns ? 1 : 0);
-        chosen.push_back(Piece{(int)i, t0, t0 + len, 0});
+        chosen.push_back(Piece{(int)i, t0, t0 + len, 0, 0});
         t0 += len;
       }
     }
-    list_schedule(chosen);
+    gang_schedule(chosen);
   } else {
-    for (size_t i = lo; i < hi; ++i) chosen.push_back(Piece{(int)i, 0, tiles[i].ntile, 0});
-    list_schedule(chosen);
+    for (size_t i = lo; i < hi; ++i) chosen.push_back(Piece{(int)i, 0, tiles[i].ntile, 0, 0});
+    gang_schedule(chosen);
     if (g_opt.split_kv == 0 && slots_left > 0) {
       const float whole_cost = price(chosen, Q, nullptr);
       int64_t total = 0;
@@ -201,7 +240,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
         int64_t pos = prev;
         while (pos < b) {
           const int64_t end = std::min<int64_t>(b, off + tiles[i].ntile);
-          cut.push_back(Piece{(int)i, (int)(pos - off), (int)(end - off), j});
+          cut.push_back(Piece{(int)i, (int)(pos - off), (int)(end - off), j, (int)cut.size()});
           pos = end;
           if (end == off + tiles[i].ntile) off += tiles[i].ntile, ++i;
         }
@@ -213,7 +252,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     }
   }
 
-  // order within a queue: longest first, input order, or shortest first
+  // order within a queue: as scheduled, input order, or shortest first
   std::vector<size_t> idx(chosen.size());
   for (size_t i = 0; i < idx.size(); ++i) idx[i] = i;
   auto len_of = [&](size_t a) { return chosen[a].t1 - chosen[a].t0; };
@@ -221,7 +260,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     if (chosen[a].queue != chosen[b].queue) return chosen[a].queue < chosen[b].queue;
     if (g_opt.order == 1) return a < b;
     if (g_opt.order == 2) return len_of(a) < len_of(b);
-    return len_of(a) > len_of(b);
+    return chosen[a].rank < chosen[b].rank;
   });
   // partial slots: the pieces of a tile take consecutive slots in key order
   std::vector<int32_t> slot_of(chosen.size(), -1);
