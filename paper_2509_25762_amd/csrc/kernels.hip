@@ -792,7 +792,9 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 // Merge the partial (max, sum, unnormalised O) of the pieces of a split tile
 // (at most kMaxSplit pieces):
 // out = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max_s m_s) * c).
-template <int D>
+// MAXS: upper bound on the pieces of any tile of the launch (4, 8 or MAXS); the per-piece
+// arrays live in registers, and fewer of them means more waves in flight to hide the loads.
+template <int D, int MAXS>
 __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
   constexpr int TPR = D / 4;          // threads per row (float4 each)
   constexpr int RPB = 256 / TPR;      // rows per block
@@ -807,9 +809,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
   // by bandwidth and not by a chain of dependent memory latencies
   const int64_t slot0 = ((int64_t)it.part0 * P.Hkv + kvh) * kTileRows + r;
   const int64_t sstride = (int64_t)P.Hkv * kTileRows;   // slots between consecutive pieces
-  float ms[kMaxSplit], ls[kMaxSplit];
+  float ms[MAXS], ls[MAXS];
 #pragma unroll
-  for (int s = 0; s < kMaxSplit; ++s) {
+  for (int s = 0; s < MAXS; ++s) {
     const bool on = s < it.nsplit;
     const float2 ml = on ? *(const float2*)(P.part_ml + (slot0 + s * sstride) * 2) : float2{-INFINITY, 0.f};
     ms[s] = ml.x;
@@ -817,25 +819,26 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
   }
   float m_max = -INFINITY;
 #pragma unroll
-  for (int s = 0; s < kMaxSplit; ++s) m_max = fmaxf(m_max, ms[s]);
+  for (int s = 0; s < MAXS; ++s) m_max = fmaxf(m_max, ms[s]);
   float l = 0.f;
 #pragma unroll
-  for (int s = 0; s < kMaxSplit; ++s) {
+  for (int s = 0; s < MAXS; ++s) {
     ms[s] = (s < it.nsplit) ? fast_exp2((ms[s] - m_max) * P.c) : 0.f;   // now the weight of piece s
     l += ms[s] * ls[s];
   }
   float4 acc = {0.f, 0.f, 0.f, 0.f};
+  constexpr int BATCH = MAXS < 8 ? MAXS : 8;
 #pragma unroll
-  for (int s0 = 0; s0 < kMaxSplit; s0 += 8) {
+  for (int s0 = 0; s0 < MAXS; s0 += BATCH) {
     if (s0 >= it.nsplit) break;
-    float4 x[8];
+    float4 x[BATCH];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < BATCH; ++j) {
       const int sj = min(s0 + j, it.nsplit - 1);   // clamped pieces carry weight 0 ... see below
       x[j] = *(const float4*)(P.part_o + (slot0 + sj * sstride) * D + d4);
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < BATCH; ++j) {
       const float w = (s0 + j < it.nsplit) ? ms[s0 + j] : 0.f;
       acc.x += w * x[j].x;
       acc.y += w * x[j].y;
@@ -972,11 +975,18 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
     for (int i = 0; i < n; ++i) P.items[i] = items[base + i];
     const int rpb = 256 / (ls.D / 4);
     dim3 grid((unsigned)(n * ls.Hkv), (unsigned)(kTileRows / rpb)), block(256);
+    int max_split = 0;
+    for (int i = 0; i < n; ++i) max_split = items[base + i].nsplit > max_split ? items[base + i].nsplit : max_split;
     prof_begin(1, st);
-    if (ls.D == 128)
-      hipLaunchKernelGGL(combine_kernel<128>, grid, block, 0, st, P);
-    else
-      hipLaunchKernelGGL(combine_kernel<64>, grid, block, 0, st, P);
+    if (ls.D == 128) {
+      if (max_split <= 4) hipLaunchKernelGGL((combine_kernel<128, 4>), grid, block, 0, st, P);
+      else if (max_split <= 8) hipLaunchKernelGGL((combine_kernel<128, 8>), grid, block, 0, st, P);
+      else hipLaunchKernelGGL((combine_kernel<128, kMaxSplit>), grid, block, 0, st, P);
+    } else {
+      if (max_split <= 4) hipLaunchKernelGGL((combine_kernel<64, 4>), grid, block, 0, st, P);
+      else if (max_split <= 8) hipLaunchKernelGGL((combine_kernel<64, 8>), grid, block, 0, st, P);
+      else hipLaunchKernelGGL((combine_kernel<64, kMaxSplit>), grid, block, 0, st, P);
+    }
     prof_end(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;

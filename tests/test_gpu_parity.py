@@ -196,6 +196,30 @@ def test_empty_batch_and_all_finished(gpu):
     run_and_check(gpu, ep, chunks, None, "zero-length passes")
 
 
+@pytest.mark.parametrize("split", [0, 1, 3])
+def test_late_dominant_keys_rerun_in_exact_mode(gpu, split):
+    """Keys far into a sequence that outscore its first keys by a wide margin: the
+    kernel's first run of such a piece (weights against the maximum of the first 32
+    keys) sees row sums beyond its limit - or plain overflow - and the piece is run
+    again in the exact mode.  Results must still match the oracle."""
+    binding, episode, torch = gpu
+    cfg = small_cfg(3, 8, 2, 128, 128, seed=4321)
+    P, R = np.array([70, 300, 33], np.int32), np.array([200, 140, 128], np.int32)
+    ep = build_episode(cfg, threads=1, lengths=(P, R))
+    one, four, sixteen, minus2 = 0x3F80, 0x4080, 0x4180, 0xC000
+    for i, spots in enumerate([[(45, four), (150, sixteen)], [(299, four), (310, minus2), (400, sixteen)], [(100, sixteen)]]):
+        lo = int(ep.tok_begin[i])
+        ep.q[lo:int(ep.tok_begin[i + 1])] = one          # every query is the all-ones vector
+        for pos, val in spots:
+            ep.k[lo + pos] = val                         # score = 128 * val * scale: +45, +181 (overflow), -23
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, split)
+    try:
+        for C in (128, 64):
+            run_and_check(gpu, ep, oracle_uniform_chunks(P, R, C), None, f"dominant keys C={C} split={split}")
+    finally:
+        binding.oppo_set_option(binding.OPT_SPLIT_KV, 0)
+
+
 def test_causality_within_last_chunk(gpu):
     """Perturb the last tokens of the final chunk: earlier rows of the same
     chunk, computed in the same launch with the same work list, do not change
