@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for the append kernel (a plain copy of known
 # size); see profiles/attn_fwd_kernel_config2.md.  Only the default workload was profiled.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 228.6e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 234.0e6}
 
 
 def cpu_baseline(cfg, ep, budget_s: float = 12.0):
@@ -77,6 +77,8 @@ def main() -> int:
     ap.add_argument("--no-workspace", action="store_true", help="disable split-KV")
     ap.add_argument("--split", type=int, default=0, help="split-KV policy (0 auto, 1 off, n forced)")
     ap.add_argument("--details", type=str, default="", help="write per-pass details to this JSON file")
+    ap.add_argument("--two-call", action="store_true",
+                    help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -113,10 +115,12 @@ def main() -> int:
     torch.cuda.synchronize()
     prompt_ms = (time.perf_counter() - t0) * 1e3 / len(copies)
 
+    fused = not args.two_call
+
     def episode(se):
         se.reset(1)
         for t in range(1, T + 1):
-            se.run_step(t)
+            se.run_step(t, fused=fused)
 
     for w in range(args.warmup):
         episode(copies[w % len(copies)])
@@ -151,7 +155,7 @@ def main() -> int:
             se = copies[s % len(copies)]
             se.reset(1)
             for t in range(1, T + 1):
-                se.run_step(t)
+                se.run_step(t, fused=fused)
                 pm, _ = ob.oppo_profile_read()
                 attn_ms[s, t - 1], merge_ms[s, t - 1], app_ms[s, t - 1] = pm["attn"], pm["merge"], pm["append"]
     ob.oppo_profile_enable(False)
@@ -167,7 +171,8 @@ def main() -> int:
         "config": {"workload": f"config {cfg.index} ({cfg.name}): B={cfg.batch}, Hq/Hkv/D={cfg.num_q_heads}/"
                                f"{cfg.num_kv_heads}/{cfg.head_dim}, C={cfg.chunk}, {T} passes per episode, "
                                f"{int(sum(w['rows'] for w in work))} response rows",
-                   "step": "one streamed episode (one oppo_chunk_step per pass: KV append + chunked-prefill attention)",
+                   "step": ("one streamed episode (one oppo_chunk_step per pass: KV append + chunked-prefill attention)"
+                            if fused else "one streamed episode (oppo_kv_append + oppo_chunk_prefill_attn per pass)"),
                    "cache_copies_rotated": len(copies)},
         "kv_read_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "total_GBps": tot_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -178,7 +183,8 @@ def main() -> int:
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.index),
-                     "algorithmic_bytes_per_launch": sum(w["kv_read_bytes"] + w["qo_bytes"] for w in work) / T,
+                     "algorithmic_bytes_per_launch": sum(w["kv_read_bytes"] + w["qo_bytes"] +
+                                                         (w["append_bytes"] if fused else 0) for w in work) / T,
                      "kernel": "attn_fwd_kernel",
                      "launches_per_step": launches_per_step, "avg_launch_ms": attn_total_ms / launches_per_step},
         "append_kernel_ms_per_step": ms["append"] / prof_steps,

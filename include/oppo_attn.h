@@ -55,7 +55,7 @@ typedef struct {
   int32_t num_q_heads;   /* Hq                                            */
   int32_t num_kv_heads;  /* Hkv, divides Hq; Hq/Hkv <= 16                  */
   int32_t head_dim;      /* D, 64 or 128                                   */
-  float softmax_scale;   /* s >= 0, finite; the configs use 1/sqrt(D)      */
+  float softmax_scale;   /* s > 0, finite; the configs use 1/sqrt(D)       */
 } oppo_attn_desc;
 
 /*

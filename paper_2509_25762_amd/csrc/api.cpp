@@ -32,14 +32,15 @@ struct Options {
 Options g_opt;
 
 // Cost model of the planner, in units of one 64-key tile of one workgroup
-// (about 2 us on MI355X): what a piece costs beyond its tiles (switching the
-// pipeline over to it), what a partial result costs on top (256 rows x (D + 2)
-// floats per kv-head written out), and the merge kernel (a launch of its own
-// plus reading the partials back).
-constexpr float kPieceTiles = 0.75f;
-constexpr float kPartialTiles = 0.5f;
-constexpr float kMergeTiles = 3.0f;
-constexpr float kMergeTilesPerPiece = 0.125f;
+// (about 1.9 us on MI355X): what a piece costs beyond its tiles (draining the
+// pipeline, writing the rows, switching over to the next piece: measured 4 to 5
+// us), what a partial result costs on top (256 rows x (D + 2) floats per kv-head
+// written out), and the merge kernel (a launch of its own, about 8 us, plus
+// reading the partials back, about 0.1 us per piece).
+constexpr float kPieceTiles = 2.0f;
+constexpr float kPartialTiles = 1.0f;
+constexpr float kMergeTiles = 4.0f;
+constexpr float kMergeTilesPerPiece = 0.06f;
 // Shortest piece the stream cut makes on purpose.
 constexpr int kMinPieceTiles = 2;
 // Upper bound on partial slots the automatic planner may ask for, per CU.
