@@ -37,7 +37,7 @@ Options g_opt;
 // us), what a partial result costs on top (256 rows x (D + 2) floats per kv-head
 // written out), and the merge kernel (a launch of its own, about 8 us, plus
 // reading the partials back, about 0.1 us per piece).
-constexpr float kPieceTiles = 2.0f;
+constexpr float kPieceTiles = 2.5f;
 constexpr float kPartialTiles = 1.0f;
 constexpr float kMergeTiles = 4.0f;
 constexpr float kMergeTilesPerPiece = 0.06f;
@@ -191,6 +191,59 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     }
   };
 
+  // Evening out a schedule of whole tiles: as long as it pays, the most loaded
+  // queue hands the end of its day to the least loaded one - its last piece as a
+  // whole if that fits into the gap, otherwise the rear part of that piece's key
+  // range, sized so that both queues end together (the tile is then merged from
+  // partial results).  Only the ends of the queues change, so the gangs further
+  // up keep running side by side.  Adds fewer than Q pieces.
+  auto even_out = [&](std::vector<Piece>& pcs, size_t max_partial) {
+    std::vector<float> load((size_t)Q, 0.f);
+    std::vector<int> n_of_tile(n, 0);
+    for (const Piece& pc : pcs) {
+      load[pc.queue] += (float)(pc.t1 - pc.t0) + kPieceTiles;
+      ++n_of_tile[pc.tile - lo];
+    }
+    size_t n_partial = 0;
+    int rank = (int)pcs.size();
+    for (int added = 0, moves = 0; added + 1 < Q && moves < 8 * Q; ++moves) {
+      int a = 0, b = 0;
+      for (int j = 1; j < Q; ++j) {
+        if (load[j] > load[a]) a = j;
+        if (load[j] < load[b]) b = j;
+      }
+      const float gap = load[a] - load[b];
+      int last = -1;   // the piece queue a runs last
+      for (size_t k = 0; k < pcs.size(); ++k)
+        if (pcs[k].queue == a && (last < 0 || pcs[k].rank > pcs[last].rank)) last = (int)k;
+      if (last < 0) break;
+      const int len = pcs[last].t1 - pcs[last].t0;
+      const bool whole = n_of_tile[pcs[last].tile - lo] == 1;
+      const float own = (float)len + kPieceTiles + (whole ? 0.f : kPartialTiles);
+      if (own < gap) {   // the whole piece moves
+        load[a] -= own;
+        load[b] += own;
+        pcs[last].queue = b;
+        pcs[last].rank = rank++;
+        continue;
+      }
+      // x key tiles move: a ends at load[a] - x (+ a partial write, if the tile was whole),
+      // b at load[b] + x + a piece boundary + a partial write
+      const float fresh = whole ? kPartialTiles : 0.f;
+      const int x = std::min((int)((gap - kPieceTiles - kPartialTiles + fresh) * 0.5f), len - kMinPieceTiles);
+      if (x < kMinPieceTiles || n_of_tile[pcs[last].tile - lo] >= oppo::kMaxSplit) break;
+      if (n_partial + (whole ? 2 : 1) > max_partial) break;
+      n_partial += whole ? 2 : 1;
+      ++n_of_tile[pcs[last].tile - lo];
+      const int t1 = pcs[last].t1;
+      pcs[last].t1 = t1 - x;
+      load[a] += fresh - (float)x;
+      load[b] += (float)x + kPieceTiles + kPartialTiles;
+      pcs.push_back(Piece{pcs[last].tile, t1 - x, t1, b, rank++});
+      ++added;
+    }
+  };
+
   const size_t slots_left = slots_avail > *next_slot ? slots_avail - *next_slot : 0;
   std::vector<Piece> chosen;
   if (g_opt.split_kv >= 2 && slots_left > 0) {
@@ -213,7 +266,13 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     for (size_t i = lo; i < hi; ++i) chosen.push_back(Piece{(int)i, 0, tiles[i].ntile, 0, 0});
     gang_schedule(chosen);
     if (g_opt.split_kv == 0 && slots_left > 0) {
-      const float whole_cost = price(chosen, Q, nullptr);
+      float whole_cost = price(chosen, Q, nullptr);
+      {
+        std::vector<Piece> evened = chosen;
+        even_out(evened, slots_left);
+        const float evened_cost = price(evened, Q, nullptr);
+        if (evened_cost < 0.97f * whole_cost) chosen.swap(evened), whole_cost = evened_cost;
+      }
       int64_t total = 0;
       int longest = 0;
       for (size_t i = lo; i < hi; ++i) total += tiles[i].ntile, longest = std::max(longest, tiles[i].ntile);

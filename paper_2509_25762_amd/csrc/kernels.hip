@@ -42,6 +42,7 @@ struct AttnParams {
   int32_t Hq, Hkv, G, TM;
   float c;
   int32_t n_queues;
+  uint32_t tm_magic;   // ceil(2^16 / TM): r / TM == (r * tm_magic) >> 16 for the rows r < 256 of a packed tile
   uint16_t first[kMaxQueues + 1];   // queue j runs pieces first[j] .. first[j+1]-1, in that order
   AttnItem items[kMaxAttnItems];
 };
@@ -252,12 +253,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   };
   // rows wave*32 + k*RPC + ln/NS of the packed tile -> (q-head of the group, token)
   auto row_of = [&](int ln, int k, int* hk, int* tk) __attribute__((always_inline)) {
-    const int R0 = (int)(wave_rows >> 10) * 32 + ln / NS;   // (wave number as a scalar)
-    const int hh0 = R0 / TM;
-    int t = R0 - hh0 * TM + k * RPC, h = hh0;
-    while (t >= TM) t -= TM, ++h;
+    const int R = (int)(wave_rows >> 10) * 32 + ln / NS + k * RPC;   // (wave number as a scalar)
+    const int h = (int)(((uint32_t)R * P.tm_magic) >> 16);           // R / TM
     *hk = h;
-    *tk = t;
+    *tk = R - h * TM;
   };
   u32x4 qraw[2][2 * IPW];   // Q row pieces on their way: [half of D][chunk]
   auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
@@ -592,7 +591,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     // lane number, see lane_now)
     const int ln_top = lane_now();
     const int r_tile = (int)(wave_rows >> 10) * 32 + (ln_top & 31);   // the lane's row of the packed tile
-    const int tok = r_tile % TM;                                      // its token within the tile
+    const int tok = r_tile - (int)(((uint32_t)r_tile * P.tm_magic) >> 16) * TM;   // its token within the tile (r_tile % TM)
     const int tokc = min(tok, tokens_of(it) - 1);
     lim = min(it.pos0 + tokc, it.k_end - 1) - 4 * (ln_top >> 5);
     min_lim = min(it.pos0, it.k_end - 1);
@@ -941,6 +940,7 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   P.TM = ls.TM;
   P.c = ls.c;
   P.n_queues = n_queues;
+  P.tm_magic = (65536u + (uint32_t)ls.TM - 1u) / (uint32_t)ls.TM;
   for (int j = 0; j <= n_queues; ++j) P.first[j] = first[j];
   for (int i = 0; i < n_items; ++i) P.items[i] = items[i];
   dim3 grid((unsigned)(n_queues * ls.Hkv));

@@ -243,3 +243,30 @@ def test_planner_splits_a_thin_tail_but_not_a_full_batch(lib):
     full = ob.oppo_plan_debug(desc, np.full(64, 700), np.full(64, 256), ws)   # 8 query tiles per queue
     assert np.all(full[:, 6] == -1) and len(full) == 256
     assert np.all(np.bincount(full[:, 7]) == 8)
+
+
+def test_planner_evens_out_the_ends_of_the_queues(lib):
+    """100 query tiles of ~20 key tiles for 32 queues: whole tiles leave queues with 3 or
+    4 of them (loads ~60 vs ~80).  The planner keeps most tiles whole and splits the last
+    pieces of the long queues so that all queues end together."""
+    desc = _desc()
+    ws = ob.oppo_workspace_bytes(desc, 64, 1 << 16)
+    rng = np.random.default_rng(11)
+    kvb = rng.integers(1000, 1400, size=25)
+    ql = np.full(25, 256)
+    ob.oppo_set_option(ob.OPT_SPLIT_KV, 1)
+    whole = ob.oppo_plan_debug(desc, kvb, ql, ws)
+    ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)
+    auto = ob.oppo_plan_debug(desc, kvb, ql, ws)
+    _check_plan(desc, kvb, ql, auto, 256 // 4)
+
+    def loads(items):
+        tiles = -(-(items[:, 5] - items[:, 4]) // 64)
+        return np.bincount(items[:, 7], weights=tiles, minlength=32)
+
+    lw, la = loads(whole), loads(auto)
+    assert lw.max() - lw.min() > 15                       # the case is uneven to begin with
+    assert la.max() <= lw.max() - 8                       # the longest queue got much shorter ...
+    assert la.max() - la.min() <= 8                       # ... and all queues end about together
+    split_tiles = len(set(map(tuple, auto[auto[:, 6] >= 0][:, :2].tolist())))
+    assert 0 < split_tiles <= 31 and np.sum(auto[:, 6] == -1) >= 100 - 31   # most tiles stay whole
