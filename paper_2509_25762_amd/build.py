@@ -9,6 +9,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboppo_attn.so")
+# stand-alone measurement of the chip's power-limited MFMA rate (not part of the library)
+CEILING_BENCH = os.path.join(HERE, "ceiling_bench")
 
 SOURCES = ["kernels.hip", "api.cpp"]
 HIP_FLAGS = [
@@ -40,6 +42,12 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    cmd = [hipcc(), "-o", CEILING_BENCH] + [f for f in HIP_FLAGS if f != "-fPIC"] + [os.path.join(CSRC, "ceiling_bench.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
     return LIB
 
 
