@@ -14,7 +14,10 @@ exactly):
                     (Sec. 3.1: the scorer processes chunk k-1 on top of the
                     chunks before it) and the streamed episode built on it;
   * schedule.py   - which rows exist at each pass of the streaming loop
-                    (Alg. 1, generation loop; Sec. 3.1).
+                    (Alg. 1, generation loop; Sec. 3.1);
+  * deferral.py   - Alg. 1's buffer of B + Delta sequences over several training
+                    iterations (Sec. 3.2): which sequences enter, stream, sit
+                    out, leave and carry their cache over, pass by pass.
 
 Pins (tests/test_oracle_*.py): brute-force triple loop on tiny inputs, a
 hand-derived two/three-token example with rational softmax weights
@@ -23,14 +26,19 @@ dominant key), the streaming-equivalence invariant of Sec. 3.1 / Eq. 3 (any
 chunking equals one-shot prefill, cache included), causality under
 perturbation of future tokens, GQA / batch-permutation / V-linearity
 invariants, and an independent float64 library routine.  The append is pinned
-by a full-buffer compare against a numpy scatter with sentinels.  No function
-here is "parity unpinned".
+by a full-buffer compare against a numpy scatter with sentinels.  The buffer
+model is pinned by a hand-worked trace of Alg. 1 (tests/golden), by its Delta = 0
+case, which must be the plain streaming schedule, and by the invariants the
+paper states (capacity, first B finishers leave, nobody starves, no token is
+recomputed or skipped).  No function here is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
 from .schedule import chunk_schedule, num_steps
+from .deferral import simulate as simulate_alg1_buffer, dense_descriptor
 
 __all__ = [
     "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
     "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
+    "simulate_alg1_buffer", "dense_descriptor",
 ]
