@@ -160,6 +160,113 @@ int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B,
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Slot pool: which sequence owns which slab of the persistent cache (Sec. 3.2;
+ * Alg. 1: the buffer holds B + Delta sequences, `Buffer.remove` takes out the B
+ * that finished first, the unfinished ones keep their cached state for the next
+ * iteration, and stage 1 fills the freed places with new sequences).
+ * The pool is host-side bookkeeping only: it never touches device memory and
+ * needs no GPU.  A pool has a fixed set of slots with capacities in tokens; the
+ * slabs are laid out back to back in that order (slot s starts at token slot
+ * capacity[0] + ... + capacity[s-1] of the caller's k / v arrays).  A slot is
+ * free or owned by one sequence, named by a caller-chosen 64-bit id.
+ * The pool object is owned by the library (create / destroy); it is not
+ * thread-safe.  All arrays in these calls are HOST memory.
+ *
+ * oppo_pool_create   : n_slots >= 0 slots, capacity[s] >= 0 tokens each.
+ * oppo_pool_destroy  : frees the pool (NULL is allowed).  A cache view made
+ *                      from it (see oppo_pool_cache) dangles afterwards.
+ * oppo_pool_acquire  : Buffer.add - gives `seq_id` the free slot with the smallest
+ *                      capacity >= max_tokens (lowest index among equals), sets
+ *                      its length to 0 and writes the slot index.  INVALID if the
+ *                      id already owns a slot, CAPACITY if no free slot is large
+ *                      enough; then nothing changes.
+ * oppo_pool_release  : Buffer.remove - the sequence's slot becomes free, its
+ *                      length 0.  The slab's bytes are left as they are: nothing
+ *                      reads a slot beyond its length.  INVALID for an unknown id.
+ * oppo_pool_slot_of  : the slot of a live sequence; INVALID for an unknown id.
+ * oppo_pool_cache    : fills *cache with a view of the pool over the caller's
+ *                      device arrays k, v (bf16 [sum of capacities][Hkv][D]):
+ *                      slot_begin and kv_len point into the pool, batch =
+ *                      n_slots.  oppo_kv_append / oppo_chunk_step advance the
+ *                      pool's lengths through it.  Valid until oppo_pool_destroy.
+ * oppo_pool_pack     : the ragged descriptor of one pass.  seq_id[n] are distinct
+ *                      live sequences, q_len[n] >= 0 their new rows; sequences
+ *                      that are not listed sit the pass out.  Writes cu_q
+ *                      [n_slots+1] (prefix sums of the per-slot row counts: rows
+ *                      are packed in slot order) and, if row_begin is not NULL,
+ *                      row_begin[j] = first row of sequence seq_id[j] in q / k_new
+ *                      / v_new / out.  INVALID for unknown or repeated ids,
+ *                      negative lengths or more than INT32_MAX rows; CAPACITY if a
+ *                      sequence's cached + new tokens exceed its slot.
+ * oppo_pool_counts   : slots, live sequences, acquisitions so far and how many
+ *                      of those took a slot that had an owner before (any pointer
+ *                      may be NULL).
+ */
+typedef struct oppo_slot_pool oppo_slot_pool;
+int oppo_pool_create(int32_t n_slots, const int32_t* capacity /* [n_slots] */, oppo_slot_pool** pool);
+int oppo_pool_destroy(oppo_slot_pool* pool);
+int oppo_pool_acquire(oppo_slot_pool* pool, int64_t seq_id, int32_t max_tokens, int32_t* slot);
+int oppo_pool_release(oppo_slot_pool* pool, int64_t seq_id);
+int oppo_pool_slot_of(const oppo_slot_pool* pool, int64_t seq_id, int32_t* slot);
+int oppo_pool_cache(oppo_slot_pool* pool, void* k, void* v, oppo_kv_cache* cache);
+int oppo_pool_pack(const oppo_slot_pool* pool, int32_t n, const int64_t* seq_id /* [n] */,
+                   const int32_t* q_len /* [n] */, int32_t* cu_q /* [n_slots+1] */,
+                   int32_t* row_begin /* [n] or NULL */);
+int oppo_pool_counts(const oppo_slot_pool* pool, int32_t* n_slots, int32_t* n_live,
+                     int64_t* n_acquired, int64_t* n_reused);
+
+/*
+ * The buffer of Alg. 1 (Sec. 3.2) as a host-side state machine: it decides which
+ * sequences the scorer serves in which pass and which sequences leave after an
+ * iteration.  It knows nothing about devices; together with a slot pool it
+ * drives oppo_chunk_step.  One training iteration is
+ *
+ *   stage 1   oppo_sched_room, then oppo_sched_add for each new sequence;
+ *   stage 2   loop { oppo_sched_begin_pass -> run the pass -> oppo_sched_end_pass }
+ *             until begin_pass reports OPPO_PASS_NONE;
+ *   stage 3   oppo_sched_end_iteration: the first B finished sequences leave.
+ *
+ * The buffer is first-in first-out and holds at most B + delta sequences.
+ * begin_pass hands out, in buffer order,
+ *   OPPO_PASS_PROMPT : the sequences added since the last pass, each with
+ *                      kv_before 0 and q_cap = its prompt length (the scorer
+ *                      prefills a prompt when the sequence enters);
+ *   OPPO_PASS_CHUNK  : every unfinished sequence with kv_before = prompt +
+ *                      response tokens streamed so far and q_cap = C - as long as
+ *                      fewer than B sequences have finished and some sequence is
+ *                      unfinished (Alg. 1, generation loop);
+ *   OPPO_PASS_NONE   : stage 2 is over.
+ * end_pass takes what the actor produced for exactly those sequences, in the
+ * same order: q_len[j] new tokens (the whole prompt in a prompt pass; 0..C in a
+ * chunk pass, and fewer than C only if the sequence ends) and finished[j] != 0 if
+ * the sequence has ended.  Sequences are recorded as finished in pass order and,
+ * within a pass, in buffer order; a finished sequence that is not among the B
+ * removed ones stays in the buffer and is first in line at the next iteration.
+ * end_iteration writes the ids that leave (at most B) and removes them; the
+ * caller releases their slots.  oppo_sched_set_delta is Buffer.set_capacity: it
+ * takes effect at the next stage 1 (a smaller capacity removes nobody).
+ * Errors: INVALID for calls out of order, unknown or misordered ids, lengths out
+ * of range; CAPACITY when adding to a full buffer.  A failed call changes nothing.
+ * All arrays are HOST memory; the object is not thread-safe.
+ */
+typedef struct oppo_scheduler oppo_scheduler;
+typedef enum { OPPO_PASS_NONE = 0, OPPO_PASS_PROMPT = 1, OPPO_PASS_CHUNK = 2 } oppo_pass_kind;
+int oppo_sched_create(int32_t B, int32_t delta, int32_t C, oppo_scheduler** sched);
+int oppo_sched_destroy(oppo_scheduler* sched);
+int oppo_sched_set_delta(oppo_scheduler* sched, int32_t delta);
+int oppo_sched_room(const oppo_scheduler* sched, int32_t* n);
+int oppo_sched_add(oppo_scheduler* sched, int64_t seq_id, int32_t prompt_len);
+int oppo_sched_begin_pass(oppo_scheduler* sched, int32_t max_n, int64_t* ids /* [max_n] */,
+                          int32_t* kv_before /* [max_n] */, int32_t* q_cap /* [max_n] */,
+                          int32_t* n, int32_t* kind);
+int oppo_sched_end_pass(oppo_scheduler* sched, int32_t n, const int64_t* ids /* [n] */,
+                        const int32_t* q_len /* [n] */, const uint8_t* finished /* [n] */);
+int oppo_sched_end_iteration(oppo_scheduler* sched, int32_t max_n, int64_t* removed /* [max_n] */,
+                             int32_t* n_removed);
+int oppo_sched_counts(const oppo_scheduler* sched, int32_t* in_buffer, int32_t* finished_waiting,
+                      int32_t* capacity);
+
+/*
  * Bytes of workspace that let the attention entry points split key ranges for
  * any call with at most max_batch sequences and max_q_tokens query rows in
  * total.  Returns 0 for an unsupported desc or negative sizes.

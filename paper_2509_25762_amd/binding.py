@@ -32,7 +32,13 @@ EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version",
     "oppo_profile_enable", "oppo_profile_read",
+    "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
+    "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
+    "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
+    "oppo_sched_begin_pass", "oppo_sched_end_pass", "oppo_sched_end_iteration", "oppo_sched_counts",
 ]
+
+PASS_NONE, PASS_PROMPT, PASS_CHUNK = 0, 1, 2
 
 
 class OppoError(RuntimeError):
@@ -90,6 +96,28 @@ def load() -> ctypes.CDLL:
     lib.oppo_profile_enable.restype = ctypes.c_int
     lib.oppo_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i32p]
     lib.oppo_profile_read.restype = ctypes.c_int
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    lib.oppo_pool_create.argtypes = [ctypes.c_int32, i32p, ctypes.POINTER(vp)]
+    lib.oppo_pool_destroy.argtypes = [vp]
+    lib.oppo_pool_acquire.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, i32p]
+    lib.oppo_pool_release.argtypes = [vp, ctypes.c_int64]
+    lib.oppo_pool_slot_of.argtypes = [vp, ctypes.c_int64, i32p]
+    lib.oppo_pool_cache.argtypes = [vp, vp, vp, ctypes.POINTER(KVCacheStruct)]
+    lib.oppo_pool_pack.argtypes = [vp, ctypes.c_int32, i64p, i32p, i32p, i32p]
+    lib.oppo_pool_counts.argtypes = [vp, i32p, i32p, i64p, i64p]
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    lib.oppo_sched_create.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(vp)]
+    lib.oppo_sched_destroy.argtypes = [vp]
+    lib.oppo_sched_set_delta.argtypes = [vp, ctypes.c_int32]
+    lib.oppo_sched_room.argtypes = [vp, i32p]
+    lib.oppo_sched_add.argtypes = [vp, ctypes.c_int64, ctypes.c_int32]
+    lib.oppo_sched_begin_pass.argtypes = [vp, ctypes.c_int32, i64p, i32p, i32p, i32p, i32p]
+    lib.oppo_sched_end_pass.argtypes = [vp, ctypes.c_int32, i64p, i32p, u8p]
+    lib.oppo_sched_end_iteration.argtypes = [vp, ctypes.c_int32, i64p, i32p]
+    lib.oppo_sched_counts.argtypes = [vp, i32p, i32p, i32p]
+    for name in EXPORTS:
+        if name.startswith("oppo_pool_") or name.startswith("oppo_sched_"):
+            getattr(lib, name).restype = ctypes.c_int
     lib.oppo_last_error.argtypes = []
     lib.oppo_last_error.restype = ctypes.c_char_p
     lib.oppo_version.argtypes = []
@@ -154,6 +182,152 @@ class KVCache:
         self.struct = KVCacheStruct(_dev_ptr(k), _dev_ptr(v),
                                     self.slot_begin.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                                     self.kv_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), self.batch)
+
+
+class SlotPool:
+    """Handle of a library-owned slot pool (see oppo_pool_create)."""
+
+    def __init__(self, handle: int, n_slots: int):
+        self.handle = handle
+        self.n_slots = n_slots
+
+
+class PoolCache:
+    """Cache view of a slot pool over caller-owned device slabs: usable wherever a
+    KVCache is.  kv_len is the pool's own length array (not a copy)."""
+
+    def __init__(self, k, v, struct: KVCacheStruct):
+        self.k, self.v, self.struct = k, v, struct
+        self.batch = struct.batch
+        self.kv_len = np.ctypeslib.as_array(struct.kv_len, shape=(max(self.batch, 1),))[: self.batch]
+        self.slot_begin = np.ctypeslib.as_array(struct.slot_begin, shape=(self.batch + 1,))
+
+
+def oppo_pool_create(capacity) -> SlotPool:
+    cap = _i32(capacity)
+    h = ctypes.c_void_p()
+    _check(load().oppo_pool_create(cap.shape[0], _i32p(cap), ctypes.byref(h)))
+    return SlotPool(h.value, cap.shape[0])
+
+
+def oppo_pool_destroy(pool: SlotPool) -> None:
+    _check(load().oppo_pool_destroy(pool.handle))
+    pool.handle = None
+
+
+def oppo_pool_acquire(pool: SlotPool, seq_id: int, max_tokens: int) -> int:
+    slot = ctypes.c_int32(-1)
+    _check(load().oppo_pool_acquire(pool.handle, seq_id, max_tokens, ctypes.byref(slot)))
+    return slot.value
+
+
+def oppo_pool_release(pool: SlotPool, seq_id: int) -> None:
+    _check(load().oppo_pool_release(pool.handle, seq_id))
+
+
+def oppo_pool_slot_of(pool: SlotPool, seq_id: int) -> int:
+    slot = ctypes.c_int32(-1)
+    _check(load().oppo_pool_slot_of(pool.handle, seq_id, ctypes.byref(slot)))
+    return slot.value
+
+
+def oppo_pool_cache(pool: SlotPool, k, v) -> PoolCache:
+    st = KVCacheStruct()
+    _check(load().oppo_pool_cache(pool.handle, _dev_ptr(k), _dev_ptr(v), ctypes.byref(st)))
+    return PoolCache(k, v, st)
+
+
+def oppo_pool_pack(pool: SlotPool, seq_id, q_len):
+    """Returns (cu_q[n_slots+1], row_begin[n]) as int32 numpy arrays."""
+    ids = np.ascontiguousarray(seq_id, dtype=np.int64)
+    ql = _i32(q_len, ids.shape[0])
+    cu_q = np.empty(pool.n_slots + 1, dtype=np.int32)
+    row_begin = np.empty(ids.shape[0], dtype=np.int32)
+    _check(load().oppo_pool_pack(pool.handle, ids.shape[0], ids.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _i32p(ql),
+                                 _i32p(cu_q), _i32p(row_begin)))
+    return cu_q, row_begin
+
+
+def oppo_pool_counts(pool: SlotPool):
+    """(n_slots, n_live, n_acquired, n_reused)."""
+    a, b = ctypes.c_int32(0), ctypes.c_int32(0)
+    c, d = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().oppo_pool_counts(pool.handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d)))
+    return a.value, b.value, c.value, d.value
+
+
+class Scheduler:
+    """Handle of a library-owned Alg. 1 buffer (see oppo_sched_create)."""
+
+    def __init__(self, handle: int, capacity: int):
+        self.handle = handle
+        self.max_n = capacity
+
+
+def _i64p(arr: np.ndarray):
+    return arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def oppo_sched_create(B: int, delta: int, C: int, max_capacity: Optional[int] = None) -> Scheduler:
+    """max_capacity: the largest B + delta the handle's output arrays are sized for."""
+    h = ctypes.c_void_p()
+    _check(load().oppo_sched_create(B, delta, C, ctypes.byref(h)))
+    return Scheduler(h.value, max(B + delta, max_capacity or 0))
+
+
+def oppo_sched_destroy(s: Scheduler) -> None:
+    _check(load().oppo_sched_destroy(s.handle))
+    s.handle = None
+
+
+def oppo_sched_set_delta(s: Scheduler, delta: int) -> None:
+    _check(load().oppo_sched_set_delta(s.handle, delta))
+
+
+def oppo_sched_room(s: Scheduler) -> int:
+    n = ctypes.c_int32(0)
+    _check(load().oppo_sched_room(s.handle, ctypes.byref(n)))
+    return n.value
+
+
+def oppo_sched_add(s: Scheduler, seq_id: int, prompt_len: int) -> None:
+    _check(load().oppo_sched_add(s.handle, seq_id, prompt_len))
+
+
+def oppo_sched_begin_pass(s: Scheduler):
+    """Returns (kind, ids int64[n], kv_before int32[n], q_cap int32[n])."""
+    ids = np.empty(s.max_n, dtype=np.int64)
+    kvb = np.empty(s.max_n, dtype=np.int32)
+    cap = np.empty(s.max_n, dtype=np.int32)
+    n, kind = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().oppo_sched_begin_pass(s.handle, s.max_n, _i64p(ids), _i32p(kvb), _i32p(cap), ctypes.byref(n),
+                                        ctypes.byref(kind)))
+    return kind.value, ids[: n.value].copy(), kvb[: n.value].copy(), cap[: n.value].copy()
+
+
+def oppo_sched_end_pass(s: Scheduler, ids, q_len, finished) -> None:
+    i = np.ascontiguousarray(ids, dtype=np.int64)
+    q = _i32(q_len, i.shape[0])
+    f = np.ascontiguousarray(finished, dtype=np.uint8)
+    if f.shape != i.shape:
+        raise ValueError("finished must have one entry per sequence")
+    _check(load().oppo_sched_end_pass(s.handle, i.shape[0], _i64p(i), _i32p(q),
+                                      f.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))))
+
+
+def oppo_sched_end_iteration(s: Scheduler) -> np.ndarray:
+    """Ids that leave the buffer (the PPO batch), in finishing order."""
+    out = np.empty(s.max_n, dtype=np.int64)
+    n = ctypes.c_int32(0)
+    _check(load().oppo_sched_end_iteration(s.handle, s.max_n, _i64p(out), ctypes.byref(n)))
+    return out[: n.value].copy()
+
+
+def oppo_sched_counts(s: Scheduler):
+    """(sequences in the buffer, finished ones waiting, capacity B + delta)."""
+    a, b, c = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().oppo_sched_counts(s.handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
 
 
 def oppo_version() -> int:

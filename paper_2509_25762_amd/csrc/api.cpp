@@ -13,9 +13,10 @@
 #include "oppo_internal.h"
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
+namespace oppo {
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -23,6 +24,10 @@ int fail(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+}  // namespace oppo
+
+namespace {
+using oppo::fail;
 
 struct Options {
   int split_kv = 0;   // 0 auto, 1 off, n>=2 forced

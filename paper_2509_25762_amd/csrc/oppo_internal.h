@@ -76,6 +76,10 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
                   const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
 const char* hip_error_string(int err);
+
+// Records the reason of a failing call (thread-local, read by oppo_last_error) and
+// returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int profile_enable(int on);
 int profile_read(double ms[3], int32_t launches[3]);  // 0 attention, 1 merge, 2 append
 

@@ -119,3 +119,139 @@ def uniform_chunks(prompt_len, resp_len, C: int) -> List[List[int]]:
         _, q_len, _ = ob.oppo_chunk_schedule(prompt_len, resp_len, C, t)
         steps.append([int(x) for x in q_len])
     return steps
+
+
+class BufferedPass:
+    """Device inputs of one scorer pass of a BufferedRun (rows packed in slot order)."""
+    __slots__ = ("iteration", "kind", "ids", "kv_before", "q_len", "cu_q", "rows", "q", "k", "v", "out")
+
+    def __init__(self, **kw):
+        for name, value in kw.items():
+            setattr(self, name, value)
+
+
+class BufferedRun:
+    """Alg. 1 with inter-step overlap over a synthetic dataset (device plumbing only).
+
+    The library's buffer state machine (oppo_sched_*) decides who is served when,
+    its slot pool (oppo_pool_*) gives each sequence in the buffer one of B + delta
+    cache slabs, and every pass is one oppo_chunk_step over all slots (sequences
+    that sit the pass out have no rows).  The "actor" is simulated: the final
+    response lengths of the dataset are known, a sequence produces min(C, what is
+    left) tokens per pass.  Sec. 3.2, Alg. 1.
+
+    The host logic runs once, in __init__, against a scheduler and a pool of its
+    own (lengths advanced by hand), to gather every pass's input rows in advance;
+    run() then replays acquisitions, passes and releases against a fresh pool, so
+    that a timed run contains library calls only.
+    """
+
+    def __init__(self, ep: Episode, B: int, delta: int, C: int, device="cuda:0", slack: int = 3,
+                 use_workspace: bool = True, max_iterations: Optional[int] = None):
+        cfg = ep.cfg
+        self.ep, self.cfg, self.device = ep, cfg, torch.device(device)
+        self.B, self.delta, self.C = B, delta, C
+        self.desc = ob.make_desc(cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.softmax_scale)
+        n = ep.prompt_len.astype(np.int64) + ep.resp_len
+        self.n_slots = B + delta
+        self.capacity = np.full(self.n_slots, int(n.max()) + slack, dtype=np.int32)
+        total = int(self.capacity.astype(np.int64).sum())
+        self.q_all = bits_to_device(ep.q, self.device)
+        self.k_all = bits_to_device(ep.k, self.device)
+        self.v_all = bits_to_device(ep.v, self.device)
+        self.cache_k = torch.full((total, cfg.num_kv_heads, cfg.head_dim), -1, dtype=torch.int16, device=self.device)
+        self.cache_v = torch.full_like(self.cache_k, -1)
+        self.out_all = torch.zeros_like(self.q_all)
+        self.workspace = None
+        self.events = []          # ("acquire", id, tokens) | ("pass", BufferedPass) | ("release", id) | ("end", iteration)
+        self.removed = []         # per iteration: ids that left
+        max_rows = self._trace(max_iterations)
+        if use_workspace:
+            nbytes = ob.oppo_workspace_bytes(self.desc, self.n_slots, max(1, max_rows))
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.pool = None
+        self.cache = None
+        self.reset()
+
+    def _trace(self, max_iterations) -> int:
+        ep = self.ep
+        P, R = ep.prompt_len, ep.resp_len
+        sched = ob.oppo_sched_create(self.B, self.delta, self.C)
+        pool = ob.oppo_pool_create(self.capacity)
+        view = ob.oppo_pool_cache(pool, 0, 0)
+        nxt, it_no, max_rows = 0, 0, 0
+        streamed = {}
+        while (nxt < len(P) or ob.oppo_sched_counts(sched)[0] > 0) and (max_iterations is None or it_no < max_iterations):
+            for _ in range(ob.oppo_sched_room(sched)):
+                if nxt == len(P):
+                    break
+                ob.oppo_sched_add(sched, nxt, int(P[nxt]))
+                ob.oppo_pool_acquire(pool, nxt, int(P[nxt]) + int(R[nxt]))
+                self.events.append(("acquire", nxt, int(P[nxt]) + int(R[nxt])))
+                streamed[nxt] = 0
+                nxt += 1
+            while True:
+                kind, ids, kvb, cap = ob.oppo_sched_begin_pass(sched)
+                if kind == ob.PASS_NONE:
+                    break
+                if kind == ob.PASS_PROMPT:
+                    q_len = cap.copy()
+                else:
+                    q_len = np.array([min(int(c), int(R[i]) - streamed[int(i)]) for i, c in zip(ids, cap)], dtype=np.int32)
+                cu_q, row_begin = ob.oppo_pool_pack(pool, ids, q_len)
+                rows = np.empty(int(cu_q[-1]), dtype=np.int64)
+                for i, b, kb, ql in zip(ids, row_begin, kvb, q_len):
+                    rows[b:b + ql] = ep.tok_begin[i] + kb + np.arange(ql)
+                    view.kv_len[ob.oppo_pool_slot_of(pool, int(i))] += ql     # what oppo_chunk_step will do
+                    if kind == ob.PASS_CHUNK:
+                        streamed[int(i)] += int(ql)
+                fin = np.array([streamed[int(i)] == R[int(i)] for i in ids], dtype=np.uint8)
+                ob.oppo_sched_end_pass(sched, ids, q_len, fin)
+                trows = torch.from_numpy(rows).to(self.device)
+                self.events.append(("pass", BufferedPass(
+                    iteration=it_no, kind=kind, ids=ids, kv_before=kvb, q_len=q_len, cu_q=cu_q, rows=trows,
+                    q=self.q_all[trows].contiguous(), k=self.k_all[trows].contiguous(), v=self.v_all[trows].contiguous(),
+                    out=torch.zeros((len(rows), self.cfg.num_q_heads, self.cfg.head_dim), dtype=torch.int16,
+                                    device=self.device))))
+                max_rows = max(max_rows, len(rows))
+            gone = ob.oppo_sched_end_iteration(sched)
+            for i in gone:
+                ob.oppo_pool_release(pool, int(i))
+                self.events.append(("release", int(i)))
+            self.removed.append([int(i) for i in gone])
+            self.events.append(("end", it_no))
+            it_no += 1
+        self.pool_counts = ob.oppo_pool_counts(pool)
+        ob.oppo_pool_destroy(pool)
+        ob.oppo_sched_destroy(sched)
+        return max_rows
+
+    def reset(self) -> None:
+        """A fresh pool over the same slabs (the slabs' old contents stay: nothing may read them)."""
+        if self.pool is not None:
+            ob.oppo_pool_destroy(self.pool)
+        self.pool = ob.oppo_pool_create(self.capacity)
+        self.cache = ob.oppo_pool_cache(self.pool, self.cache_k, self.cache_v)
+
+    def passes(self) -> List[BufferedPass]:
+        return [e[1] for e in self.events if e[0] == "pass"]
+
+    def run(self, stream=None, upto_iteration: Optional[int] = None) -> None:
+        """Replays the run from a fresh pool (see reset): every pass is one oppo_chunk_step.
+        upto_iteration = k stops after iteration k's sequences have left."""
+        for e in self.events:
+            if e[0] == "acquire":
+                ob.oppo_pool_acquire(self.pool, e[1], e[2])
+            elif e[0] == "release":
+                ob.oppo_pool_release(self.pool, e[1])
+            elif e[0] == "pass":
+                p = e[1]
+                ob.oppo_chunk_step(self.desc, self.cache, p.cu_q, p.q, p.k, p.v, p.out, self.workspace, stream)
+            elif e[0] == "end" and upto_iteration is not None and e[1] >= upto_iteration:
+                return
+
+    def scatter_outputs(self) -> torch.Tensor:
+        for p in self.passes():
+            if len(p.rows):
+                self.out_all[p.rows] = p.out
+        return self.out_all
