@@ -66,6 +66,66 @@ def cpu_baseline(cfg, ep, budget_s: float = 12.0):
     }
 
 
+def deferral_bench(args, cfg, torch, ob) -> int:
+    """Alg. 1 with B + Delta slots over a dataset of 2 x batch sequences (see --deferral)."""
+    import dataclasses
+    from paper_2509_25762_amd.episode import BufferedRun
+    from paper_2509_25762_amd.workload import build_episode, episode_work
+    delta = args.deferral
+    if delta >= cfg.batch:
+        print("bench.py: --deferral needs DELTA < batch", file=sys.stderr)
+        return 2
+    data_cfg = dataclasses.replace(cfg, batch=2 * cfg.batch)
+    ep = build_episode(data_cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    B = cfg.batch - delta
+    runs = [BufferedRun(ep, B, delta, cfg.chunk) for _ in range(2)]
+    passes = runs[0].passes()
+    work = episode_work(cfg, [(p.kv_before, p.q_len) for p in passes])
+    flops = sum(w["flops"] for w in work)
+    tot_bytes = sum(w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"] for w in work)
+    steps, warmup = max(1, args.steps // 4), max(1, args.warmup // 4)   # a run is ~4 episodes' worth of work
+    for w in range(warmup):
+        runs[w % 2].reset()
+        runs[w % 2].run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        runs[s % 2].reset()
+        runs[s % 2].run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ob.oppo_profile_enable(True)
+    ob.oppo_profile_read()
+    prof_steps = min(steps, 12)
+    for s in range(prof_steps):
+        runs[s % 2].reset()
+        runs[s % 2].run()
+    kms, n = ob.oppo_profile_read()
+    ob.oppo_profile_enable(False)
+    achieved = flops / (kms["attn"] / prof_steps * 1e-3) / 1e12
+    n_iter = len(runs[0].removed)
+    line = {
+        "metric": "chunked-prefill attn TFLOP/s + KV GB/s, % of MI355X roofline, 1 GPU",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}) with inter-step overlap: {2 * cfg.batch} sequences through "
+                               f"{cfg.batch} cache slots, B={B}, Delta={delta}, C={cfg.chunk}, {n_iter} iterations, "
+                               f"{len(passes)} passes (prompt passes included), {int(sum(w['rows'] for w in work))} rows",
+                   "step": "the whole run: slot acquisitions, one oppo_chunk_step per pass, releases",
+                   "slot_reuses": int(runs[0].pool_counts[3])},
+        "total_GBps": tot_bytes / (ms * 1e-3) / 1e9,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "kernel": "attn_fwd_kernel",
+                     "launches_per_step": n["attn"] / prof_steps,
+                     "avg_launch_ms": kms["attn"] / max(1, n["attn"])},
+        "merge_kernel_ms_per_step": kms["merge"] / prof_steps,
+        "cpu_baseline": None,
+    }
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +137,10 @@ def main() -> int:
     ap.add_argument("--no-workspace", action="store_true", help="disable split-KV")
     ap.add_argument("--split", type=int, default=0, help="split-KV policy (0 auto, 1 off, n forced)")
     ap.add_argument("--details", type=str, default="", help="write per-pass details to this JSON file")
+    ap.add_argument("--deferral", type=int, default=-1, metavar="DELTA",
+                    help="inter-step overlap instead of one episode: a dataset of twice the workload's sequences "
+                         "streamed through batch cache slots, B = batch - DELTA of which finish per iteration "
+                         "(Alg. 1); every pass, the prompts' included, is one oppo_chunk_step over all slots")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
@@ -96,6 +160,8 @@ def main() -> int:
     if args.split:
         ob.oppo_set_option(ob.OPT_SPLIT_KV, args.split)
     cfg = CONFIGS[args.config]
+    if args.deferral >= 0:
+        return deferral_bench(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
     T = len(chunks) - 1
