@@ -17,7 +17,8 @@ exactly):
                     (Alg. 1, generation loop; Sec. 3.1);
   * deferral.py   - Alg. 1's buffer of B + Delta sequences over several training
                     iterations (Sec. 3.2): which sequences enter, stream, sit
-                    out, leave and carry their cache over, pass by pass.
+                    out, leave and carry their cache over, pass by pass;
+  * tuner.py      - the periodic search over candidate chunk sizes (Sec. 3.1).
 
 Pins (tests/test_oracle_*.py): brute-force triple loop on tiny inputs, a
 hand-derived two/three-token example with rational softmax weights
@@ -30,15 +31,17 @@ by a full-buffer compare against a numpy scatter with sentinels.  The buffer
 model is pinned by a hand-worked trace of Alg. 1 (tests/golden), by its Delta = 0
 case, which must be the plain streaming schedule, and by the invariants the
 paper states (capacity, first B finishers leave, nobody starves, no token is
-recomputed or skipped).  No function here is "parity unpinned".
+recomputed or skipped); the tuner by a hand-worked run and by the argmin
+property over random step times.  No function here is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
 from .schedule import chunk_schedule, num_steps
 from .deferral import simulate as simulate_alg1_buffer, dense_descriptor
+from .tuner import ChunkTunerOracle, run_tuner
 
 __all__ = [
     "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
     "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
-    "simulate_alg1_buffer", "dense_descriptor",
+    "simulate_alg1_buffer", "dense_descriptor", "ChunkTunerOracle", "run_tuner",
 ]
