@@ -66,6 +66,71 @@ def cpu_baseline(cfg, ep, budget_s: float = 12.0):
     }
 
 
+def chunk_sweep(args, cfg, torch, ob) -> int:
+    """The intra-step trade-off in the scorer's own terms (Sec. 3.1; Sec. 4.4, chunk-size ablation):
+    small chunks cost GPU time (more passes, more fixed cost per pass), large chunks leave a long last
+    pass that starts only when generation has ended and so cannot be hidden behind it."""
+    import dataclasses
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import build_episode, episode_work
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    candidates = [64, 128, 256, 512, 1024]
+    rows = []
+    for C in candidates:
+        chunks = uniform_chunks(ep.prompt_len, ep.resp_len, C)
+        T = len(chunks) - 1
+        copies = [StreamedEpisode(ep, chunks) for _ in range(2)]
+        work = episode_work(dataclasses.replace(cfg, chunk=C), [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
+        flops = sum(w["flops"] for w in work)
+        for se in copies:
+            se.reset(0)
+            se.run_step(0)
+
+        def episode(se):
+            se.reset(1)
+            for t in range(1, T + 1):
+                se.run_step(t)
+
+        steps, warmup = max(8, args.steps // 4), max(8, args.warmup // 2)
+        for w in range(warmup):
+            episode(copies[w % 2])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s_ in range(steps):
+            episode(copies[s_ % 2])
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        # the last pass on its own (library events around its launches)
+        ob.oppo_profile_enable(True)
+        last = 0.0
+        for s_ in range(8):
+            se = copies[s_ % 2]
+            se.reset(1)
+            for t in range(1, T):
+                se.run_step(t)
+            ob.oppo_profile_read()
+            se.run_step(T)
+            kms, _ = ob.oppo_profile_read()
+            last += (kms["attn"] + kms["merge"]) / 8
+        ob.oppo_profile_enable(False)
+        rows.append({"chunk": C, "passes": T, "episode_ms": ms, "tflops": flops / (ms * 1e-3) / 1e12, "last_pass_ms": last})
+        del copies
+        torch.cuda.empty_cache()
+    # the tuner, fed with (scorer time that competes with generation for the GPU) + (tail that cannot overlap)
+    tuner = ob.oppo_tuner_create(candidates, 50)
+    picked = None
+    for step in range(len(candidates) + 1):
+        c = ob.oppo_tuner_chunk(tuner, step)
+        r = rows[candidates.index(c)]
+        ob.oppo_tuner_report(tuner, step, (r["episode_ms"] + r["last_pass_ms"]) * 1e-3)
+        picked = c
+    ob.oppo_tuner_destroy(tuner)
+    print(json.dumps({"metric": "streamed episode vs chunk size", "config": {"workload": f"config {cfg.index} ({cfg.name}) lengths, "
+                      f"B={cfg.batch}, chunk sizes {candidates}"}, "sweep": rows,
+                      "tuner_objective": "episode_ms + last_pass_ms", "tuner_pick": picked, "n_gpus": 1, "data": "synthetic"}))
+    return 0
+
+
 def deferral_bench(args, cfg, torch, ob) -> int:
     """Alg. 1 with B + Delta slots over a dataset of 2 x batch sequences (see --deferral)."""
     import dataclasses
@@ -141,6 +206,9 @@ def main() -> int:
                     help="inter-step overlap instead of one episode: a dataset of twice the workload's sequences "
                          "streamed through batch cache slots, B = batch - DELTA of which finish per iteration "
                          "(Alg. 1); every pass, the prompts' included, is one oppo_chunk_step over all slots")
+    ap.add_argument("--chunk-sweep", action="store_true",
+                    help="time the workload's streamed episode for chunk sizes 64..1024 (total scorer time and the "
+                         "last pass, which cannot overlap generation) and let the chunk-size tuner pick")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
@@ -162,6 +230,8 @@ def main() -> int:
     cfg = CONFIGS[args.config]
     if args.deferral >= 0:
         return deferral_bench(args, cfg, torch, ob)
+    if args.chunk_sweep:
+        return chunk_sweep(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
     T = len(chunks) - 1

@@ -267,6 +267,24 @@ int oppo_sched_counts(const oppo_scheduler* sched, int32_t* in_buffer, int32_t* 
                       int32_t* capacity);
 
 /*
+ * Periodic search for the chunk size C (Sec. 3.1, "Dynamic Control on Intra-step
+ * Overlap"): training steps are numbered 0, 1, 2, ...; every `period` steps a
+ * window starts whose first steps try the candidates, one step each, in the
+ * order given (at most `period` of them); every later step of the window uses
+ * the candidate whose trial step of this window was reported fastest (the first
+ * listed among equals; a trial without a report counts as infinitely slow).
+ * oppo_tuner_chunk  : the chunk size for training step `step`.
+ * oppo_tuner_report : the wall time of a finished step, in seconds (>= 0).
+ * Host-side state machine, no GPU; not thread-safe.  INVALID for null pointers,
+ * no candidates, candidates < 1, period < 1, negative steps or times.
+ */
+typedef struct oppo_chunk_tuner oppo_chunk_tuner;
+int oppo_tuner_create(int32_t n, const int32_t* candidates /* [n] */, int32_t period, oppo_chunk_tuner** tuner);
+int oppo_tuner_destroy(oppo_chunk_tuner* tuner);
+int oppo_tuner_chunk(const oppo_chunk_tuner* tuner, int64_t step, int32_t* chunk);
+int oppo_tuner_report(oppo_chunk_tuner* tuner, int64_t step, double seconds);
+
+/*
  * Bytes of workspace that let the attention entry points split key ranges for
  * any call with at most max_batch sequences and max_q_tokens query rows in
  * total.  Returns 0 for an unsupported desc or negative sizes.

@@ -36,6 +36,7 @@ EXPORTS = [
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
     "oppo_sched_begin_pass", "oppo_sched_end_pass", "oppo_sched_end_iteration", "oppo_sched_counts",
+    "oppo_tuner_create", "oppo_tuner_destroy", "oppo_tuner_chunk", "oppo_tuner_report",
 ]
 
 PASS_NONE, PASS_PROMPT, PASS_CHUNK = 0, 1, 2
@@ -115,8 +116,12 @@ def load() -> ctypes.CDLL:
     lib.oppo_sched_end_pass.argtypes = [vp, ctypes.c_int32, i64p, i32p, u8p]
     lib.oppo_sched_end_iteration.argtypes = [vp, ctypes.c_int32, i64p, i32p]
     lib.oppo_sched_counts.argtypes = [vp, i32p, i32p, i32p]
+    lib.oppo_tuner_create.argtypes = [ctypes.c_int32, i32p, ctypes.c_int32, ctypes.POINTER(vp)]
+    lib.oppo_tuner_destroy.argtypes = [vp]
+    lib.oppo_tuner_chunk.argtypes = [vp, ctypes.c_int64, i32p]
+    lib.oppo_tuner_report.argtypes = [vp, ctypes.c_int64, ctypes.c_double]
     for name in EXPORTS:
-        if name.startswith("oppo_pool_") or name.startswith("oppo_sched_"):
+        if name.startswith(("oppo_pool_", "oppo_sched_", "oppo_tuner_")):
             getattr(lib, name).restype = ctypes.c_int
     lib.oppo_last_error.argtypes = []
     lib.oppo_last_error.restype = ctypes.c_char_p
@@ -328,6 +333,35 @@ def oppo_sched_counts(s: Scheduler):
     a, b, c = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
     _check(load().oppo_sched_counts(s.handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
     return a.value, b.value, c.value
+
+
+class ChunkTuner:
+    """Handle of a library-owned chunk-size tuner (see oppo_tuner_create)."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+
+def oppo_tuner_create(candidates, period: int) -> ChunkTuner:
+    c = _i32(candidates)
+    h = ctypes.c_void_p()
+    _check(load().oppo_tuner_create(c.shape[0], _i32p(c), period, ctypes.byref(h)))
+    return ChunkTuner(h.value)
+
+
+def oppo_tuner_destroy(t: ChunkTuner) -> None:
+    _check(load().oppo_tuner_destroy(t.handle))
+    t.handle = None
+
+
+def oppo_tuner_chunk(t: ChunkTuner, step: int) -> int:
+    c = ctypes.c_int32(0)
+    _check(load().oppo_tuner_chunk(t.handle, step, ctypes.byref(c)))
+    return c.value
+
+
+def oppo_tuner_report(t: ChunkTuner, step: int, seconds: float) -> None:
+    _check(load().oppo_tuner_report(t.handle, step, seconds))
 
 
 def oppo_version() -> int:

@@ -1,9 +1,11 @@
 // The buffer of Alg. 1 as a host-side state machine: which sequences the scorer
 // serves in which pass, which leave after the iteration and which carry over.
 // (Sec. 3.2, Alg. 1 stages 1-3.  No device work, no GPU needed.)
+#include <math.h>
 #include <stdint.h>
 
 #include <algorithm>
+#include <iterator>
 #include <unordered_map>
 #include <vector>
 
@@ -162,6 +164,71 @@ int oppo_sched_counts(const oppo_scheduler* s, int32_t* in_buffer, int32_t* fini
   if (in_buffer) *in_buffer = (int32_t)s->buffer.size();
   if (finished_waiting) *finished_waiting = (int32_t)s->finished_order.size();
   if (capacity) *capacity = s->B + s->delta;
+  return OPPO_OK;
+}
+
+// ---- periodic chunk-size search (Sec. 3.1, dynamic control on intra-step overlap) ----
+
+}  // extern "C"
+
+struct oppo_chunk_tuner {
+  std::vector<int32_t> candidates;
+  int32_t period;
+  std::unordered_map<int64_t, double> seconds;   // training step -> reported step time
+  int32_t trials() const { return std::min<int32_t>((int32_t)candidates.size(), period); }
+};
+
+extern "C" {
+
+int oppo_tuner_create(int32_t n, const int32_t* candidates, int32_t period, oppo_chunk_tuner** tuner) {
+  if (!tuner) return fail(OPPO_ERR_INVALID, "tuner is null");
+  *tuner = nullptr;
+  if (n < 1 || !candidates) return fail(OPPO_ERR_INVALID, "at least one candidate chunk size is needed");
+  if (period < 1) return fail(OPPO_ERR_INVALID, "period=%d must be positive", period);
+  for (int32_t j = 0; j < n; ++j)
+    if (candidates[j] < 1) return fail(OPPO_ERR_INVALID, "candidate %d is %d", j, candidates[j]);
+  oppo_chunk_tuner* t = new oppo_chunk_tuner();
+  t->candidates.assign(candidates, candidates + n);
+  t->period = period;
+  *tuner = t;
+  return OPPO_OK;
+}
+
+int oppo_tuner_destroy(oppo_chunk_tuner* tuner) {
+  delete tuner;
+  return OPPO_OK;
+}
+
+int oppo_tuner_chunk(const oppo_chunk_tuner* t, int64_t step, int32_t* chunk) {
+  if (!t || !chunk) return fail(OPPO_ERR_INVALID, "tuner or chunk is null");
+  if (step < 0) return fail(OPPO_ERR_INVALID, "step is negative");
+  const int64_t start = (step / t->period) * t->period;
+  const int64_t k = step - start;
+  if (k < t->trials()) {
+    *chunk = t->candidates[(size_t)k];
+    return OPPO_OK;
+  }
+  int32_t best = 0;
+  double best_s = INFINITY;
+  for (int32_t j = 0; j < t->trials(); ++j) {
+    auto it = t->seconds.find(start + j);
+    const double sj = it == t->seconds.end() ? INFINITY : it->second;
+    if (sj < best_s) best = j, best_s = sj;
+  }
+  *chunk = t->candidates[(size_t)best];
+  return OPPO_OK;
+}
+
+int oppo_tuner_report(oppo_chunk_tuner* t, int64_t step, double seconds) {
+  if (!t) return fail(OPPO_ERR_INVALID, "tuner is null");
+  if (step < 0 || !(seconds >= 0.0)) return fail(OPPO_ERR_INVALID, "bad report (step %lld, %g s)", (long long)step, seconds);
+  // only trial steps decide anything; older windows are forgotten
+  const int64_t start = (step / t->period) * t->period;
+  if (step - start < t->trials()) {
+    for (auto it = t->seconds.begin(); it != t->seconds.end();)
+      it = it->first < start - t->period ? t->seconds.erase(it) : std::next(it);
+    t->seconds[step] = seconds;
+  }
   return OPPO_OK;
 }
 

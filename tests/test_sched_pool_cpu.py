@@ -161,3 +161,39 @@ def test_pool_never_gives_one_slot_to_two_live_sequences(lib):
             live[10_000 + step] = slot
         assert len(set(live.values())) == len(live) == ob.oppo_pool_counts(pool)[1]
     ob.oppo_pool_destroy(pool)
+
+
+def test_chunk_tuner_matches_the_oracle(lib):
+    from oracle.tuner import run_tuner
+    rng = np.random.default_rng(8)
+    for trial in range(40):
+        k = int(rng.integers(1, 6))
+        cands = [int(x) for x in rng.choice(np.arange(1, 40) * 32, size=k, replace=False)]
+        period = int(rng.integers(1, 12))
+        n = 150
+        cost = np.round(rng.random((n, k)) * 4) / 4 + 0.25          # coarse values: ties do occur
+        want = run_tuner(cands, period, lambda t, c: cost[t][cands.index(c)], n)
+        tuner = ob.oppo_tuner_create(cands, period)
+        got = []
+        for t in range(n):
+            c = ob.oppo_tuner_chunk(tuner, t)
+            got.append(c)
+            ob.oppo_tuner_report(tuner, t, float(cost[t][cands.index(c)]))
+        ob.oppo_tuner_destroy(tuner)
+        assert got == want
+
+
+def test_chunk_tuner_rejects_bad_arguments(lib):
+    for cands, period in (([], 5), ([128, 0], 5), ([128], 0)):
+        with pytest.raises(ob.OppoError):
+            ob.oppo_tuner_create(cands, period)
+    tuner = ob.oppo_tuner_create([64, 128], 4)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_tuner_chunk(tuner, -1)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_tuner_report(tuner, 0, -1.0)
+    with pytest.raises(ob.OppoError):
+        ob.oppo_tuner_report(tuner, 0, float("nan"))
+    ob.oppo_tuner_report(tuner, 1, 0.5)                             # only the second trial was timed
+    assert [ob.oppo_tuner_chunk(tuner, t) for t in range(8)] == [64, 128, 128, 128, 64, 128, 64, 64]
+    ob.oppo_tuner_destroy(tuner)
