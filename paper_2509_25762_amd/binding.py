@@ -70,6 +70,12 @@ def load() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2509_25762_amd.build`")
+    try:
+        # torch ships its own HIP runtime; it has to be the first one loaded into the process,
+        # or the library's kernels and torch's buffers end up on two different runtimes
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     i32p = ctypes.POINTER(ctypes.c_int32)
     vp = ctypes.c_void_p
