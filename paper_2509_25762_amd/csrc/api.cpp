@@ -110,12 +110,14 @@ struct QTile { int seq; int32_t j0, n_tok, keys, ntile; };
 // Plan one launch for the query tiles [lo, hi).
 //
 // The kernel runs one persistent workgroup per (queue, kv-head); the planner
-// decides which pieces each queue runs.  Two ways of filling the queues are
-// priced with the cost model above and the cheaper one is taken:
+// decides which pieces each queue runs.  Three ways of filling the queues are
+// priced with the cost model above and the cheapest one is taken:
 //   * whole tiles, sequence by sequence onto the least loaded group of queues (see
 //     gang_schedule) - no partial results, but the longest tile bounds the
 //     makespan and with few tiles per queue the loads are uneven (the thin tail
 //     passes of a long-tailed batch);
+//   * the same with the ends of the queues evened out (see even_out): a few tiles
+//     are split, most stay whole;
 //   * the tiles' key ranges laid end to end and cut into equal shares, one per
 //     queue: a tile that straddles a cut is split there (on a 64-key boundary)
 //     and its pieces are merged afterwards.  A cut that falls close to a tile
