@@ -131,6 +131,82 @@ def chunk_sweep(args, cfg, torch, ob) -> int:
     return 0
 
 
+def contention_study(args, cfg, torch, ob) -> int:
+    """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
+    colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
+    per compute unit it is given, so the split of the chip is a launch parameter: with fewer CUs for the
+    scorer, the other stream's kernels find free CUs instead of waiting for whole launches to end."""
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import build_episode, episode_work
+    dev = torch.device("cuda:0")
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
+    T = len(chunks) - 1
+    copies = [StreamedEpisode(ep, chunks) for _ in range(2)]
+    work = episode_work(cfg, [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
+    flops = sum(w["flops"] for w in work)
+    for se in copies:
+        se.reset(0)
+        se.run_step(0)
+    # decode-like load: a sweep over 16 weight matrices of 8192 x 8192 bf16 (2 GiB in all), one
+    # matrix-vector product each - bound by reading the weights, like a decoding step at small batch
+    W = [torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16) for _ in range(16)]
+    x = torch.randn(8192, device=dev, dtype=torch.bfloat16)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def attn(n):
+        for i in range(n):
+            se = copies[i % 2]
+            se.reset(1)
+            for t in range(1, T + 1):
+                se.run_step(t, stream=sa)
+
+    def decode(n):
+        with torch.cuda.stream(sb):
+            for _ in range(n):
+                for w in W:
+                    torch.mv(w, x)
+
+    def timed(fa, fb, na, nb):
+        torch.cuda.synchronize()
+        ea0, ea1, eb0, eb1 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+        ea0.record(sa), eb0.record(sb)
+        # enqueue in small slices so that both streams always have work queued
+        ia = ib = 0
+        while ia < na or ib < nb:
+            if ia < na and fa:
+                fa(min(4, na - ia))
+            ia += 4
+            if ib < nb and fb:
+                fb(min(4, nb - ib))
+            ib += 4
+        ea1.record(sa), eb1.record(sb)
+        torch.cuda.synchronize()
+        return ea0.elapsed_time(ea1), eb0.elapsed_time(eb1)
+
+    rows = []
+    n_ep, n_dec = 120, 60
+    for cus in (256, 192, 128):
+        ob.oppo_set_option(ob.OPT_NUM_CUS, cus)
+        timed(attn, decode, 40, 20)                      # warm-up
+        a_alone, _ = timed(attn, None, n_ep, 0)
+        _, d_alone = timed(None, decode, 0, n_dec)
+        a_both, d_both = timed(attn, decode, n_ep, n_dec)
+        rows.append({"attention_cus": cus,
+                     "episode_ms_alone": a_alone / n_ep, "episode_ms_colocated": a_both / n_ep,
+                     "tflops_alone": flops / (a_alone / n_ep * 1e-3) / 1e12,
+                     "tflops_colocated": flops / (a_both / n_ep * 1e-3) / 1e12,
+                     "decode_sweep_ms_alone": d_alone / n_dec, "decode_sweep_ms_colocated": d_both / n_dec,
+                     "decode_GBps_alone": 16 * 8192 * 8192 * 2 / (d_alone / n_dec * 1e-3) / 1e9,
+                     "decode_GBps_colocated": 16 * 8192 * 8192 * 2 / (d_both / n_dec * 1e-3) / 1e9})
+    ob.oppo_set_option(ob.OPT_NUM_CUS, 256)
+    print(json.dumps({"metric": "colocation of chunked prefill with a memory-bound load", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}) episode on one stream; 16 x (8192 x 8192 bf16 "
+                                             "matrix-vector product) sweeps on another; default stream priorities"},
+                      "rows": rows}))
+    return 0
+
+
 def deferral_bench(args, cfg, torch, ob) -> int:
     """Alg. 1 with B + Delta slots over a dataset of 2 x batch sequences (see --deferral)."""
     import dataclasses
@@ -209,6 +285,10 @@ def main() -> int:
     ap.add_argument("--chunk-sweep", action="store_true",
                     help="time the workload's streamed episode for chunk sizes 64..1024 (total scorer time and the "
                          "last pass, which cannot overlap generation) and let the chunk-size tuner pick")
+    ap.add_argument("--contention", action="store_true",
+                    help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
+                         "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
+                         "restricted to 256 / 192 / 128 compute units (OPPO_OPT_NUM_CUS)")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
@@ -232,6 +312,8 @@ def main() -> int:
         return deferral_bench(args, cfg, torch, ob)
     if args.chunk_sweep:
         return chunk_sweep(args, cfg, torch, ob)
+    if args.contention:
+        return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
     T = len(chunks) - 1
