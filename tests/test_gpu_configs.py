@@ -149,3 +149,42 @@ def test_full_size_config(gpu, idx):
           flush=True)
     assert err.max() <= MAX_ABS
     assert err.mean() <= MEAN_ABS
+
+
+@pytest.mark.timeout(600)
+def test_very_long_context(gpu):
+    """One sequence of 66,000 tokens next to a short one: key ranges of more than a thousand
+    64-key tiles (cut into the maximum of 32 pieces on the thin response passes), token rows
+    beyond 2^16, a prompt of 1029 query tiles in one call.  Sampled rows against the oracle,
+    all rows against the device's one-shot prefill, cache bit-exact."""
+    from paper_2509_25762_amd.workload import Config
+    binding, episode, torch = gpu
+    cfg = Config(0, "long-context", 31337, 2, 4, 2, 128, 256, ("fixed", 1), ("fixed", 1))
+    P = np.array([65700, 900], dtype=np.int32)
+    R = np.array([300, 40], dtype=np.int32)
+    ep = build_episode(cfg, threads=8, lengths=(P, R))
+    chunks = oracle_chunks(P, R, cfg.chunk)
+    print(f"long context: {int(ep.tok_begin[-1])} tokens, {len(chunks) - 1} response passes", flush=True)
+    se = episode.StreamedEpisode(ep, chunks)
+    se.run()
+    torch.cuda.synchronize()
+    out_dev = se.scatter_outputs()
+    out = out_dev.cpu().numpy().view(np.uint16)
+    for i in range(2):
+        lo, hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        b = int(se.slot_begin[i])
+        assert torch.equal(se.cache_k[b:b + hi - lo], se.k_all[lo:hi]) and torch.equal(se.cache_v[b:b + hi - lo], se.v_all[lo:hi])
+    full = se.full_prefill()
+    torch.cuda.synchronize()
+    diff = (out_dev.view(torch.bfloat16).float() - full.view(torch.bfloat16).float()).abs()
+    assert float(diff.max()) <= MAX_ABS and float(diff.mean()) <= MEAN_ABS
+    rng = np.random.default_rng(5)
+    n0 = int(P[0] + R[0])
+    positions = sorted(set([0, 1, 63, 64, 65535, 65536, int(P[0]) - 1, int(P[0]), int(P[0]) + 255, int(P[0]) + 256, n0 - 1])
+                       | set(int(x) for x in rng.integers(0, n0, size=40)))
+    orc = RowOracle(ep, 0)
+    ref = orc.rows(positions, [0, 1, 2, 3])
+    got = bf16_bits_to_f64(out[orc.lo + np.asarray(positions)][:, [0, 1, 2, 3]])
+    err = np.abs(got - ref)
+    print(f"long context: max abs err {err.max():.3e} mean {err.mean():.3e} over {err.size} elements", flush=True)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
