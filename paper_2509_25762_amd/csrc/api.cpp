@@ -251,6 +251,53 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
     }
   };
 
+  // Whole pieces change queues while that shortens the longest queue: the most loaded
+  // queue gives a piece to the least loaded one, or the two exchange a pair.  (Greedy
+  // placement of a handful of pieces per queue leaves the loads a few per cent apart.)
+  // A piece keeps its place in the scheduling order, so on its new queue it still runs at
+  // about the time its gang does.
+  auto swap_pieces = [&](std::vector<Piece>& pcs) {
+    std::vector<float> load((size_t)Q, 0.f);
+    for (const Piece& pc : pcs) load[pc.queue] += (float)(pc.t1 - pc.t0) + kPieceTiles;
+    for (int round = 0; round < 4 * Q; ++round) {
+      int a = 0, b = 0;
+      for (int j = 1; j < Q; ++j) {
+        if (load[j] > load[a]) a = j;
+        if (load[j] < load[b]) b = j;
+      }
+      float best = load[a] - 0.5f;   // a move has to gain at least half a tile
+      int bx = -1, by = -1;
+      // (the pieces of one sequence stay on different queues)
+      auto holds = [&](int queue, int seq, int except) {
+        for (size_t z = 0; z < pcs.size(); ++z)
+          if (pcs[z].queue == queue && (int)z != except && tiles[pcs[z].tile].seq == seq) return true;
+        return false;
+      };
+      for (size_t x = 0; x < pcs.size(); ++x) {
+        if (pcs[x].queue != a) continue;
+        const float cx = (float)(pcs[x].t1 - pcs[x].t0) + kPieceTiles;
+        const int sx = tiles[pcs[x].tile].seq;
+        if (std::max(load[a] - cx, load[b] + cx) < best && !holds(b, sx, -1))
+          best = std::max(load[a] - cx, load[b] + cx), bx = (int)x, by = -1;
+        for (size_t y = 0; y < pcs.size(); ++y) {
+          if (pcs[y].queue != b) continue;
+          const float cy = (float)(pcs[y].t1 - pcs[y].t0) + kPieceTiles;
+          const float m = std::max(load[a] - cx + cy, load[b] + cx - cy);
+          if (m < best && !holds(b, sx, (int)y) && !holds(a, tiles[pcs[y].tile].seq, (int)x)) best = m, bx = (int)x, by = (int)y;
+        }
+      }
+      if (bx < 0) break;
+      const float cx = (float)(pcs[bx].t1 - pcs[bx].t0) + kPieceTiles;
+      load[a] -= cx, load[b] += cx;
+      pcs[bx].queue = b;
+      if (by >= 0) {
+        const float cy = (float)(pcs[by].t1 - pcs[by].t0) + kPieceTiles;
+        load[b] -= cy, load[a] += cy;
+        pcs[by].queue = a;
+      }
+    }
+  };
+
   const size_t slots_left = slots_avail > *next_slot ? slots_avail - *next_slot : 0;
   std::vector<Piece> chosen;
   if (g_opt.split_kv >= 2 && slots_left > 0) {
@@ -272,6 +319,7 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
   } else {
     for (size_t i = lo; i < hi; ++i) chosen.push_back(Piece{(int)i, 0, tiles[i].ntile, 0, 0});
     gang_schedule(chosen);
+    swap_pieces(chosen);
     if (g_opt.split_kv == 0 && slots_left > 0) {
       float whole_cost = price(chosen, Q, nullptr);
       {
