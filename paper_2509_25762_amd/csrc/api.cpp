@@ -40,12 +40,12 @@ Options g_opt;
 // (about 1.9 us on MI355X): what a piece costs beyond its tiles (draining the
 // pipeline, writing the rows, switching over to the next piece: measured 4 to 5
 // us), what a partial result costs on top (256 rows x (D + 2) floats per kv-head
-// written out), and the merge kernel (a launch of its own, about 8 us, plus
-// reading the partials back, about 0.1 us per piece).
+// written out), and the merge kernel (a launch of its own plus reading the
+// partials back: its measured duration fits 4 us + 0.17 us per piece).
 constexpr float kPieceTiles = 2.5f;
 constexpr float kPartialTiles = 1.0f;
-constexpr float kMergeTiles = 4.0f;
-constexpr float kMergeTilesPerPiece = 0.06f;
+constexpr float kMergeTiles = 2.5f;
+constexpr float kMergeTilesPerPiece = 0.1f;
 // Shortest piece the stream cut makes on purpose.
 constexpr int kMinPieceTiles = 2;
 // Upper bound on partial slots the automatic planner may ask for, per CU.
