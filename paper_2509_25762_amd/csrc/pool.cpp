@@ -37,6 +37,7 @@ int oppo_pool_create(int32_t n_slots, const int32_t* capacity, oppo_slot_pool** 
   p->capacity.assign(capacity, capacity + n_slots);
   p->slot_begin.assign((size_t)n_slots + 1, 0);
   for (int32_t s = 0; s < n_slots; ++s) p->slot_begin[s + 1] = p->slot_begin[s] + capacity[s];
+  p->kv_len.reserve(1);   // (so that even an empty pool hands out a non-null length array)
   p->kv_len.assign((size_t)n_slots, 0);
   p->owner.assign((size_t)n_slots, 0);
   p->live.assign((size_t)n_slots, 0);
