@@ -258,7 +258,25 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
   // about the time its gang does.
   auto swap_pieces = [&](std::vector<Piece>& pcs) {
     std::vector<float> load((size_t)Q, 0.f);
-    for (const Piece& pc : pcs) load[pc.queue] += (float)(pc.t1 - pc.t0) + kPieceTiles;
+    std::vector<std::vector<int>> on((size_t)Q);   // pieces of each queue
+    for (size_t x = 0; x < pcs.size(); ++x) {
+      load[pcs[x].queue] += (float)(pcs[x].t1 - pcs[x].t0) + kPieceTiles;
+      on[pcs[x].queue].push_back((int)x);
+    }
+    auto cost = [&](int x) { return (float)(pcs[x].t1 - pcs[x].t0) + kPieceTiles; };
+    // (the pieces of one sequence stay on different queues)
+    auto holds = [&](int queue, int seq, int except) {
+      for (int z : on[queue])
+        if (z != except && tiles[pcs[z].tile].seq == seq) return true;
+      return false;
+    };
+    auto move = [&](int x, int from, int to) {
+      std::vector<int>& f = on[from];
+      f.erase(std::find(f.begin(), f.end(), x));
+      on[to].push_back(x);
+      pcs[x].queue = to;
+      load[from] -= cost(x), load[to] += cost(x);
+    };
     for (int round = 0; round < 4 * Q; ++round) {
       int a = 0, b = 0;
       for (int j = 1; j < Q; ++j) {
@@ -267,34 +285,20 @@ void plan_launch(const oppo::LayerShape& ls, const std::vector<SeqView>& seqs, c
       }
       float best = load[a] - 0.5f;   // a move has to gain at least half a tile
       int bx = -1, by = -1;
-      // (the pieces of one sequence stay on different queues)
-      auto holds = [&](int queue, int seq, int except) {
-        for (size_t z = 0; z < pcs.size(); ++z)
-          if (pcs[z].queue == queue && (int)z != except && tiles[pcs[z].tile].seq == seq) return true;
-        return false;
-      };
-      for (size_t x = 0; x < pcs.size(); ++x) {
-        if (pcs[x].queue != a) continue;
-        const float cx = (float)(pcs[x].t1 - pcs[x].t0) + kPieceTiles;
+      for (int x : on[a]) {
+        const float cx = cost(x);
         const int sx = tiles[pcs[x].tile].seq;
         if (std::max(load[a] - cx, load[b] + cx) < best && !holds(b, sx, -1))
-          best = std::max(load[a] - cx, load[b] + cx), bx = (int)x, by = -1;
-        for (size_t y = 0; y < pcs.size(); ++y) {
-          if (pcs[y].queue != b) continue;
-          const float cy = (float)(pcs[y].t1 - pcs[y].t0) + kPieceTiles;
+          best = std::max(load[a] - cx, load[b] + cx), bx = x, by = -1;
+        for (int y : on[b]) {
+          const float cy = cost(y);
           const float m = std::max(load[a] - cx + cy, load[b] + cx - cy);
-          if (m < best && !holds(b, sx, (int)y) && !holds(a, tiles[pcs[y].tile].seq, (int)x)) best = m, bx = (int)x, by = (int)y;
+          if (m < best && !holds(b, sx, y) && !holds(a, tiles[pcs[y].tile].seq, x)) best = m, bx = x, by = y;
         }
       }
       if (bx < 0) break;
-      const float cx = (float)(pcs[bx].t1 - pcs[bx].t0) + kPieceTiles;
-      load[a] -= cx, load[b] += cx;
-      pcs[bx].queue = b;
-      if (by >= 0) {
-        const float cy = (float)(pcs[by].t1 - pcs[by].t0) + kPieceTiles;
-        load[b] -= cy, load[a] += cy;
-        pcs[by].queue = a;
-      }
+      move(bx, a, b);
+      if (by >= 0) move(by, b, a);
     }
   };
 
