@@ -293,3 +293,26 @@ def test_snapshot_restore_resumes_identically(gpu):
     for a, s in zip(first, se.steps):
         assert torch.equal(a, s.out)
     assert torch.equal(final_k, se.cache_k)
+
+
+@pytest.mark.parametrize("gain,split", [(4.0, 0), (4.0, 3), (8.0, 0)])
+def test_peaked_softmax_moves_the_reference_often(gpu, gain, split):
+    """Queries and keys scaled up so that logits spread over +-40 nats and more: the weights
+    of a column span hundreds of bits, and the running reference of the softmax has to be
+    moved again and again in the middle of pieces, of the tile that straddles the cache
+    boundary in the fused call, and of split pieces that are merged with very different
+    references.  (Inputs are N(0,1) bf16 times a power of two: still exact bf16.)"""
+    binding, episode, torch = gpu
+    cfg = small_cfg(3, 8, 2, 128, 80, seed=2718)
+    ep = build_episode(cfg, threads=2, lengths=(np.array([300, 70, 1], np.int32), np.array([260, 500, 90], np.int32)))
+    scale_bits = int(np.log2(gain)) << 7                        # bf16 exponent field starts at bit 7
+    for t in (ep.q, ep.k):
+        nz = (t & 0x7F80) != 0                                  # zeros and subnormals stay as they are
+        t[nz] = (t[nz] + scale_bits).astype(np.uint16)
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, split)
+    try:
+        se, out, (mx, mean) = run_and_check(gpu, ep, oracle_uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk), None,
+                                            f"peaked gain={gain} split={split}")
+    finally:
+        binding.oppo_set_option(binding.OPT_SPLIT_KV, 0)
+    print(f"peaked softmax gain {gain}: max abs err {mx:.3e}, mean {mean:.3e}")
