@@ -1,7 +1,8 @@
 // gfx950 kernels: ragged chunked-prefill attention, split-KV merge, KV append.
 //
 // Attention (per workgroup = one AttnItem x one kv-head), 8 waves of 64 lanes:
-//   * the query tile packs TM tokens x G q-heads of the kv-head into 256 rows;
+//   * the query tile packs TM tokens x G q-heads of the kv-head into 256 rows
+//     (row r = head r % G of token r / G);
 //     wave w owns rows [32w, 32w+32).  The transposed product S^T = K Q^T is
 //     computed with v_mfma_f32_32x32x16_bf16 (K as the A operand from LDS, Q^T
 //     as the B operand held in registers), so one lane owns one query column:
@@ -42,7 +43,7 @@ struct AttnParams {
   int32_t Hq, Hkv, G, TM;
   float c;
   int32_t n_queues;
-  uint32_t tm_magic;   // ceil(2^16 / TM): r / TM == (r * tm_magic) >> 16 for the rows r < 256 of a packed tile
+  uint32_t g_magic;    // ceil(2^16 / G): r / G == (r * g_magic) >> 16 for the rows r < 256 of a packed tile
   uint16_t first[kMaxQueues + 1];   // queue j runs pieces first[j] .. first[j+1]-1, in that order
   AttnItem items[kMaxAttnItems];
 };
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     return r;
   };
 
-  // ---- this lane's query column (row of the packed (head, token) tile) --------------
+  // ---- this lane's query column (row of the packed (token, head) tile) --------------
   bf16x8 qf[KK];
 
   // ---- cooperative K/V tile loads ------------------------------------------------
@@ -251,12 +252,14 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     return (((row / RPC) / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
            (uint32_t)(((row / RPC) % IPW) * 8192 + (row % RPC) * RB);
   };
-  // rows wave*32 + k*RPC + ln/NS of the packed tile -> (q-head of the group, token)
+  // rows wave*32 + k*RPC + ln/NS of the packed tile -> (q-head of the group, token):
+  // row R is head R % G of token R / G, so the rows of a tile of n tokens are the
+  // first n * G ones (and rows from TM * G on, if G does not divide 256, are never used)
   auto row_of = [&](int ln, int k, int* hk, int* tk) __attribute__((always_inline)) {
     const int R = (int)(wave_rows >> 10) * 32 + ln / NS + k * RPC;   // (wave number as a scalar)
-    const int h = (int)(((uint32_t)R * P.tm_magic) >> 16);           // R / TM
-    *hk = h;
-    *tk = R - h * TM;
+    const int t = (int)(((uint32_t)R * P.g_magic) >> 16);            // R / G
+    *tk = t;
+    *hk = R - t * G;
   };
   u32x4 qraw[2][2 * IPW];   // Q row pieces on their way: [half of D][chunk]
   auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       int hk, tk;
       row_of(ln, k, &hk, &tk);
       // rows beyond the tile repeat a valid row; their columns are never stored
-      const uint16_t* qp = P.q + ((int64_t)(a.q_row0 + min(tk, tokens_of(a) - 1)) * Hq + kvh * G + min(hk, G - 1)) * D + (ln % NS) * 8;
+      const uint16_t* qp = P.q + ((int64_t)(a.q_row0 + min(tk, tokens_of(a) - 1)) * Hq + kvh * G + hk) * D + (ln % NS) * 8;
 #pragma unroll
       for (int h = 0; h < 2; ++h) qraw[h][k] = *(const u32x4*)(qp + h * (D / 2));
     }
@@ -566,6 +569,14 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // its start and awaited at its end, before the barrier after which the next
   // iteration starts reading the tile in between.
   int U = 0;
+  // A wave whose 32 rows all lie beyond the tile's tokens (a short tile fills the
+  // first n_tok * G rows only) does none of the arithmetic of the piece: it still
+  // requests its share of every key tile and joins the barriers, and leaves the
+  // matrix and vector units of its SIMD to the waves that have rows.
+  auto has_rows = [&](const AttnItem& a) __attribute__((always_inline)) -> bool {
+    return (int)(wave_rows >> 10) * 32 < tokens_of(a) * G;
+  };
+  bool act = true;
   auto iteration = [&](auto TC, int t) __attribute__((always_inline)) {
     constexpr int ts = decltype(TC)::value;
     issue_next((ts + 2) % NSTAGE);
@@ -576,6 +587,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   };
 
   // ---- start-up: Q of the first piece, the first two tiles of the stream ------------
+  act = has_rows(it);
   q_request(it);
   issue_next(0);
   issue_next(1);
@@ -591,7 +603,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     // lane number, see lane_now)
     const int ln_top = lane_now();
     const int r_tile = (int)(wave_rows >> 10) * 32 + (ln_top & 31);   // the lane's row of the packed tile
-    const int tok = r_tile - (int)(((uint32_t)r_tile * P.tm_magic) >> 16) * TM;   // its token within the tile (r_tile % TM)
+    const int tok = (int)(((uint32_t)r_tile * P.g_magic) >> 16);     // its token within the tile (r_tile / G)
     const int tokc = min(tok, tokens_of(it) - 1);
     lim = min(it.pos0 + tokc, it.k_end - 1) - 4 * (ln_top >> 5);
     min_lim = min(it.pos0, it.k_end - 1);
@@ -610,9 +622,14 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "=v"(o[db]));
 
+    // Whatever this wave still has in flight (the previous piece's stores, the tiles
+    // requested ahead) is awaited here, on the path of every wave: left to the compiler,
+    // the wait for the stores ends up inside the key loop, where it would cover each
+    // newly requested tile as well.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     // S^T of unit 0 on its own, then the operand buffers as the first body expects
     // them.  The ring stage is a run-time value here (and only here and in the drain).
-    {
+    if (act) {
       const int off0 = ph * TILE_BYTES;
       const int offm = ((ph + 3) & 3) * TILE_BYTES;   // "unit -1": any stage, see unit_body
 #pragma unroll
@@ -635,11 +652,20 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
     // tiles of the piece, the loop unrolled over the four ring stages
     const int tau1 = ph + nt;
-    for (int tb = 0; tb < tau1; tb += 4) {
-      if (tb >= ph) iteration(std::integral_constant<int, 0>{}, tb - ph);
-      if (tb + 1 >= ph && tb + 1 < tau1) iteration(std::integral_constant<int, 1>{}, tb + 1 - ph);
-      if (tb + 2 >= ph && tb + 2 < tau1) iteration(std::integral_constant<int, 2>{}, tb + 2 - ph);
-      if (tb + 3 >= ph && tb + 3 < tau1) iteration(std::integral_constant<int, 3>{}, tb + 3 - ph);
+    if (act) {
+      for (int tb = 0; tb < tau1; tb += 4) {
+        if (tb >= ph) iteration(std::integral_constant<int, 0>{}, tb - ph);
+        if (tb + 1 >= ph && tb + 1 < tau1) iteration(std::integral_constant<int, 1>{}, tb + 1 - ph);
+        if (tb + 2 >= ph && tb + 2 < tau1) iteration(std::integral_constant<int, 2>{}, tb + 2 - ph);
+        if (tb + 3 >= ph && tb + 3 < tau1) iteration(std::integral_constant<int, 3>{}, tb + 3 - ph);
+      }
+    } else {
+      // (the same requests, waits and barriers as `iteration`, nothing else)
+      for (int t = 0; t < nt; ++t) {
+        issue_next((ph + t + 2) & 3);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        wg_barrier();
+      }
     }
 
     // request the next piece's Q rows; they are collected after the epilogue
@@ -647,6 +673,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     const bool more = p + 1 < p_last;
     if (more) {
       it = piece(p + 1);
+      act = has_rows(it);
       q_request(it);
     } else {
       // (defined on every path, so that the values are not kept alive across the key loop)
@@ -724,7 +751,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       for (int k = 0; k < 2 * IPW; ++k) {
         int hk, tk;
         row_of(ln, k, &hk, &tk);
-        grow[k] = (hk < G && tk < tokens_of(done)) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
+        grow[k] = tk < tokens_of(done) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
       }
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -801,9 +828,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams P) {
   const int kvh = blockIdx.x % P.Hkv;
   const int r = blockIdx.y * RPB + threadIdx.x / TPR;
   const int d4 = (threadIdx.x % TPR) * 4;
-  const int hh = r / P.TM;
-  const int tok = r - hh * P.TM;
-  if (hh >= P.G || tok >= it.n_tok) return;
+  const int tok = r / P.G;    // row r of the packed tile is head r % G of token r / G
+  const int hh = r - tok * P.G;
+  if (tok >= it.n_tok) return;
   // all loads of a batch are issued before the first use, so the merge is bound
   // by bandwidth and not by a chain of dependent memory latencies
   const int64_t slot0 = ((int64_t)it.part0 * P.Hkv + kvh) * kTileRows + r;
@@ -940,7 +967,7 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   P.TM = ls.TM;
   P.c = ls.c;
   P.n_queues = n_queues;
-  P.tm_magic = (65536u + (uint32_t)ls.TM - 1u) / (uint32_t)ls.TM;
+  P.g_magic = (65536u + (uint32_t)ls.G - 1u) / (uint32_t)ls.G;
   for (int j = 0; j <= n_queues; ++j) P.first[j] = first[j];
   for (int i = 0; i < n_items; ++i) P.items[i] = items[i];
   dim3 grid((unsigned)(n_queues * ls.Hkv));

@@ -188,6 +188,36 @@ def test_split_kv_and_order_do_not_change_results(gpu, split, order):
         binding.oppo_set_option(binding.OPT_ORDER, 0)
 
 
+@pytest.mark.parametrize("G,D,split", [(1, 128, 0), (3, 128, 0), (4, 128, 3), (5, 64, 0), (8, 128, 0), (16, 64, 3)])
+def test_short_tiles_leave_waves_without_rows(gpu, G, D, split):
+    """Steps whose chunks fill 1, 2, ... of the 8 waves' 32-row blocks of a packed tile
+    (a tile of n tokens has n * G rows), next to full tiles, on contexts of several
+    key tiles: every count of waves with rows occurs, with the key range whole and cut."""
+    binding, episode, torch = gpu
+    tm = 256 // G
+    per_wave = max(1, 32 // G)
+    q_lens = sorted({1, per_wave, per_wave + 1, 3 * per_wave, 5 * per_wave - 1, tm - 1, tm, tm + 1})
+    B = len(q_lens)
+    P = np.array([130 + 37 * i for i in range(B)], np.int32)
+    R = np.array([3 * q for q in q_lens], np.int32)
+    cfg = small_cfg(B, 2 * G, 2, D, 64, seed=700 + G)
+    ep = build_episode(cfg, threads=2, lengths=(P, R))
+    # prompts first, then three steps in which sequence i gets q_lens[(i + step) % B] rows
+    chunks = [[int(p) for p in P]]
+    left = R.astype(np.int64).copy()
+    step = 0
+    while left.any():
+        take = [int(min(left[i], q_lens[(i + step) % B])) for i in range(B)]
+        left -= np.array(take)
+        chunks.append(take)
+        step += 1
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, split)
+    try:
+        run_and_check(gpu, ep, chunks, None, f"short tiles G={G} D={D} split={split}")
+    finally:
+        binding.oppo_set_option(binding.OPT_SPLIT_KV, 0)
+
+
 def test_empty_batch_and_all_finished(gpu):
     binding, episode, torch = gpu
     cfg = small_cfg(3, 8, 2, 128, 32)
