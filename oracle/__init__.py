@@ -18,7 +18,10 @@ exactly):
   * deferral.py   - Alg. 1's buffer of B + Delta sequences over several training
                     iterations (Sec. 3.2): which sequences enter, stream, sit
                     out, leave and carry their cache over, pass by pass;
-  * tuner.py      - the periodic search over candidate chunk sizes (Sec. 3.1).
+  * tuner.py      - the periodic search over candidate chunk sizes (Sec. 3.1);
+  * overlap.py    - the timeline of intra-step overlap (Sec. 3.1): when the scorer
+                    works on which chunk while the actor decodes the next one, and
+                    how much scoring time stays exposed at the end of the step.
 
 Pins (tests/test_oracle_*.py): brute-force triple loop on tiny inputs, a
 hand-derived two/three-token example with rational softmax weights
@@ -32,16 +35,21 @@ model is pinned by a hand-worked trace of Alg. 1 (tests/golden), by its Delta = 
 case, which must be the plain streaming schedule, and by the invariants the
 paper states (capacity, first B finishers leave, nobody starves, no token is
 recomputed or skipped); the tuner by a hand-worked run and by the argmin
-property over random step times.  No function here is "parity unpinned".
+property over random step times; the overlap timeline by hand-worked cases
+(tests/golden), a tick-by-tick simulation on integer durations and its closed
+forms (a scorer that keeps up exposes only the last chunk; one that never
+idles ends at gen[0] + sum(score)).  No function here is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
 from .schedule import chunk_schedule, num_steps
 from .deferral import simulate as simulate_alg1_buffer, dense_descriptor
 from .tuner import ChunkTunerOracle, run_tuner
+from .overlap import timeline as overlap_timeline, sequential_step
 
 __all__ = [
     "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
     "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
     "simulate_alg1_buffer", "dense_descriptor", "ChunkTunerOracle", "run_tuner",
+    "overlap_timeline", "sequential_step",
 ]
