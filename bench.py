@@ -12,6 +12,7 @@ Prints ONE JSON line (see README for the field meanings).
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -128,6 +129,78 @@ def chunk_sweep(args, cfg, torch, ob) -> int:
     print(json.dumps({"metric": "streamed episode vs chunk size", "config": {"workload": f"config {cfg.index} ({cfg.name}) lengths, "
                       f"B={cfg.batch}, chunk sizes {candidates}"}, "sweep": rows,
                       "tuner_objective": "episode_ms + last_pass_ms", "tuner_pick": picked, "n_gpus": 1, "data": "synthetic"}))
+    return 0
+
+
+def overlap_study(args, cfg, torch, ob) -> int:
+    """Intra-step overlap in the paper's own quantity (Sec. 3.1): how much of the scorer's time is
+    hidden behind generation, and the step time that results, per chunk size.  The scorer's
+    attention passes are measured here (library events around each pass's kernels, times the
+    model's layer count); the generating side and the dense part of the scorer's layers come from
+    the stated synthetic model (workload.TimingModel).  The two sides are taken to run on separate
+    accelerators.  The prompts are chunk 0 of the timeline, complete at time 0 (they are known before
+    generation starts).  Baseline: generation, then one prefill of everything."""
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import TimingModel, build_episode, generation_times
+    model = TimingModel()
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    candidates = [16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
+    reps = 5
+    ob.oppo_profile_enable(True)
+    resp_tokens = float(np.sum(ep.resp_len))
+    all_tokens = float(np.sum(ep.prompt_len) + np.sum(ep.resp_len))
+    # baseline scoring: one prefill of prompt + response
+    se = StreamedEpisode(ep, uniform_chunks(ep.prompt_len, ep.resp_len, 1 << 20))
+    once_ms = 0.0
+    for r in range(reps + 1):
+        ob.oppo_profile_read()
+        se.full_prefill()
+        kms, _ = ob.oppo_profile_read()
+        if r:
+            once_ms += (kms["attn"] + kms["merge"]) / reps
+    del se
+    torch.cuda.empty_cache()
+    score_once_s = model.layers * once_ms * 1e-3 + model.dense_s(all_tokens)
+    rows = []
+    for C in candidates:
+        chunks = uniform_chunks(ep.prompt_len, ep.resp_len, C)
+        T = len(chunks) - 1
+        se = StreamedEpisode(ep, chunks)
+        pass_ms = np.zeros(T + 1)
+        for r in range(reps + 1):
+            se.reset(0)
+            for t in range(T + 1):
+                ob.oppo_profile_read()
+                se.run_step(t)
+                kms, _ = ob.oppo_profile_read()
+                if r:
+                    pass_ms[t] += (kms["attn"] + kms["merge"] + kms["append"]) / reps
+        gen_s = [0.0] + generation_times(ep.prompt_len, ep.resp_len, C, model)
+        assert len(gen_s) == T + 1
+        tokens = np.array([float(np.sum(st.q_len)) for st in se.steps])
+        score_s = model.layers * pass_ms * 1e-3 + np.array([model.dense_s(x) for x in tokens])
+        _, _, summ = ob.oppo_overlap_timeline(gen_s, score_s)
+        sequential = float(np.sum(gen_s)) - (T - 1) * model.handoff_s + score_once_s   # one hand-off, at the end
+        rows.append({"chunk": C, "passes": T, "generation_s": float(np.sum(gen_s)), "scoring_s": float(np.sum(score_s)),
+                     "attention_s": float(model.layers * pass_ms.sum() * 1e-3), "exposed_s": summ["exposed"],
+                     "hidden_frac": 1.0 - summ["exposed"] / float(np.sum(score_s)), "step_s": summ["step_end"],
+                     "sequential_s": sequential, "speedup": sequential / summ["step_end"]})
+        del se
+        torch.cuda.empty_cache()
+    ob.oppo_profile_enable(False)
+    tuner = ob.oppo_tuner_create(candidates, 50)
+    picked = None
+    for step in range(len(candidates) + 1):
+        c = ob.oppo_tuner_chunk(tuner, step)
+        ob.oppo_tuner_report(tuner, step, rows[candidates.index(c)]["step_s"])
+        picked = c
+    ob.oppo_tuner_destroy(tuner)
+    print(json.dumps({"metric": "modelled step time with intra-step overlap vs chunk size",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}) lengths, B={cfg.batch}, chunk sizes {candidates}"},
+                      "model": dataclasses.asdict(model), "score_once_attention_ms_per_layer": once_ms,
+                      "sweep": rows, "tuner_pick": picked, "n_gpus": 1, "data": "synthetic",
+                      "note": "attention passes measured, everything else from the stated model; response tokens "
+                              f"{int(resp_tokens)}, all tokens {int(all_tokens)}"}))
     return 0
 
 
@@ -285,6 +358,10 @@ def main() -> int:
     ap.add_argument("--chunk-sweep", action="store_true",
                     help="time the workload's streamed episode for chunk sizes 64..1024 (total scorer time and the "
                          "last pass, which cannot overlap generation) and let the chunk-size tuner pick")
+    ap.add_argument("--overlap", action="store_true",
+                    help="intra-step overlap as a timeline: measured attention passes of the scorer (x 32 layers) "
+                         "against a stated synthetic model of the generating side, per chunk size 16..2048: "
+                         "hidden fraction of the scoring time, step time, speed-up over generate-then-score")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -312,6 +389,8 @@ def main() -> int:
         return deferral_bench(args, cfg, torch, ob)
     if args.chunk_sweep:
         return chunk_sweep(args, cfg, torch, ob)
+    if args.overlap:
+        return overlap_study(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))

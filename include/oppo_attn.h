@@ -285,6 +285,23 @@ int oppo_tuner_chunk(const oppo_chunk_tuner* tuner, int64_t step, int32_t* chunk
 int oppo_tuner_report(oppo_chunk_tuner* tuner, int64_t step, double seconds);
 
 /*
+ * Timeline of intra-step overlap (Sec. 3.1): the actor decodes its chunks back to
+ * back from time 0, chunk k taking gen_s[k]; the scorer takes the chunks in order,
+ * one at a time, chunk k taking score_s[k], and starts chunk k once the actor has
+ * completed it and chunk k-1 has been scored.  Writes when the scorer starts and
+ * ends each chunk; summary[0] = end of generation, summary[1] = end of the step
+ * (the later of the two sides), summary[2] = exposed scoring time (end of step
+ * minus end of generation).  Feeding it measured pass times of the scorer and the
+ * decode times of the generating side turns kernel time into the quantity the
+ * technique is about: scoring latency hidden behind generation.
+ * All arrays are HOST memory, n_chunks entries each (summary: 3), caller-owned;
+ * start_s / end_s may be null.  n_chunks = 0 gives an all-zero summary.
+ * INVALID for a negative count, null inputs or summary, negative or NaN times.
+ */
+int oppo_overlap_timeline(int32_t n_chunks, const double* gen_s, const double* score_s,
+                          double* start_s, double* end_s, double* summary /* [3] */);
+
+/*
  * Bytes of workspace that let the attention entry points split key ranges for
  * any call with at most max_batch sequences and max_q_tokens query rows in
  * total.  Returns 0 for an unsupported desc or negative sizes.

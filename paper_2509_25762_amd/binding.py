@@ -36,7 +36,7 @@ EXPORTS = [
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
     "oppo_sched_begin_pass", "oppo_sched_end_pass", "oppo_sched_end_iteration", "oppo_sched_counts",
-    "oppo_tuner_create", "oppo_tuner_destroy", "oppo_tuner_chunk", "oppo_tuner_report",
+    "oppo_tuner_create", "oppo_tuner_destroy", "oppo_tuner_chunk", "oppo_tuner_report", "oppo_overlap_timeline",
 ]
 
 PASS_NONE, PASS_PROMPT, PASS_CHUNK = 0, 1, 2
@@ -126,6 +126,8 @@ def load() -> ctypes.CDLL:
     lib.oppo_tuner_destroy.argtypes = [vp]
     lib.oppo_tuner_chunk.argtypes = [vp, ctypes.c_int64, i32p]
     lib.oppo_tuner_report.argtypes = [vp, ctypes.c_int64, ctypes.c_double]
+    lib.oppo_overlap_timeline.argtypes = [ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.oppo_overlap_timeline.restype = ctypes.c_int
     for name in EXPORTS:
         if name.startswith(("oppo_pool_", "oppo_sched_", "oppo_tuner_")):
             getattr(lib, name).restype = ctypes.c_int
@@ -368,6 +370,18 @@ def oppo_tuner_chunk(t: ChunkTuner, step: int) -> int:
 
 def oppo_tuner_report(t: ChunkTuner, step: int, seconds: float) -> None:
     _check(load().oppo_tuner_report(t.handle, step, seconds))
+
+
+def oppo_overlap_timeline(gen_s, score_s):
+    """Returns (start_s, end_s, {"gen_end", "step_end", "exposed"}) of the scorer's work on each chunk."""
+    g = np.ascontiguousarray(np.asarray(gen_s, dtype=np.float64))
+    sc = np.ascontiguousarray(np.asarray(score_s, dtype=np.float64))
+    if g.shape != sc.shape or g.ndim != 1:
+        raise ValueError("gen_s and score_s must be 1-d arrays of one length")
+    start, end, summary = np.zeros_like(g), np.zeros_like(g), np.zeros(3, dtype=np.float64)
+    _check(load().oppo_overlap_timeline(g.shape[0], g.ctypes.data, sc.ctypes.data, start.ctypes.data,
+                                        end.ctypes.data, summary.ctypes.data))
+    return start, end, {"gen_end": float(summary[0]), "step_end": float(summary[1]), "exposed": float(summary[2])}
 
 
 def oppo_version() -> int:

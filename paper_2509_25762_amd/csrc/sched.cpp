@@ -232,4 +232,30 @@ int oppo_tuner_report(oppo_chunk_tuner* t, int64_t step, double seconds) {
   return OPPO_OK;
 }
 
+// ---------------------------------------------------------------------------------------
+// Intra-step overlap as a two-stage pipeline (Sec. 3.1): chunk k reaches the scorer when
+// the actor has decoded it; the scorer works through the chunks in order.
+
+int oppo_overlap_timeline(int32_t n, const double* gen_s, const double* score_s, double* start_s,
+                          double* end_s, double* summary) {
+  if (n < 0) return fail(OPPO_ERR_INVALID, "negative chunk count %d", n);
+  if (!summary || (n > 0 && (!gen_s || !score_s))) return fail(OPPO_ERR_INVALID, "null argument");
+  for (int32_t k = 0; k < n; ++k)
+    if (!(gen_s[k] >= 0.0) || !(score_s[k] >= 0.0))
+      return fail(OPPO_ERR_INVALID, "chunk %d: bad times (decode %g s, scoring %g s)", k, gen_s[k], score_s[k]);
+  double decoded = 0.0;   // when the actor completes the current chunk
+  double scored = 0.0;    // when the scorer completes the previous one
+  for (int32_t k = 0; k < n; ++k) {
+    decoded += gen_s[k];
+    const double begin = decoded > scored ? decoded : scored;
+    scored = begin + score_s[k];
+    if (start_s) start_s[k] = begin;
+    if (end_s) end_s[k] = scored;
+  }
+  summary[0] = decoded;
+  summary[1] = scored > decoded ? scored : decoded;
+  summary[2] = summary[1] - decoded;
+  return OPPO_OK;
+}
+
 }  // extern "C"

@@ -197,3 +197,36 @@ def test_chunk_tuner_rejects_bad_arguments(lib):
     ob.oppo_tuner_report(tuner, 1, 0.5)                             # only the second trial was timed
     assert [ob.oppo_tuner_chunk(tuner, t) for t in range(8)] == [64, 128, 128, 128, 64, 128, 64, 64]
     ob.oppo_tuner_destroy(tuner)
+
+
+def test_overlap_timeline_matches_the_oracle(lib):
+    from oracle.overlap import timeline
+    rng = np.random.default_rng(2024)
+    for trial in range(200):
+        n = int(rng.integers(0, 12))
+        gen = rng.uniform(0.0, 3.0, n) * (rng.random(n) > 0.1)
+        score = rng.uniform(0.0, 3.0, n) * (rng.random(n) > 0.1)
+        start, end, summ = ob.oppo_overlap_timeline(gen, score)
+        want = timeline(gen.tolist(), score.tolist())
+        # same additions in the same order on both sides except the prefix sums of gen
+        assert np.allclose(start, want["start"], rtol=1e-13, atol=1e-13)
+        assert np.allclose(end, want["end"], rtol=1e-13, atol=1e-13)
+        for key in ("gen_end", "step_end", "exposed"):
+            assert summ[key] == pytest.approx(want[key], rel=1e-13, abs=1e-13)
+
+
+def test_overlap_timeline_rejects_bad_arguments(lib):
+    import ctypes
+    summary = (ctypes.c_double * 3)()
+    one = (ctypes.c_double * 1)(1.0)
+    neg = (ctypes.c_double * 1)(-1.0)
+    nan = (ctypes.c_double * 1)(float("nan"))
+    f = lib.oppo_overlap_timeline
+    assert f(-1, one, one, None, None, summary) == ob.OPPO_ERR_INVALID
+    assert f(1, None, one, None, None, summary) == ob.OPPO_ERR_INVALID
+    assert f(1, one, one, None, None, None) == ob.OPPO_ERR_INVALID
+    assert f(1, neg, one, None, None, summary) == ob.OPPO_ERR_INVALID
+    assert f(1, one, nan, None, None, summary) == ob.OPPO_ERR_INVALID
+    assert "chunk 0" in ob.oppo_last_error()
+    assert f(1, one, one, None, None, summary) == ob.OPPO_OK and list(summary) == [1.0, 2.0, 1.0]
+    assert f(0, None, None, None, None, summary) == ob.OPPO_OK and list(summary) == [0.0, 0.0, 0.0]
