@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for the append kernel (a plain copy of known
 # size); see profiles/attn_fwd_kernel_config2.md and profiles/attn_fwd_kernel_config3_traffic.md.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 258.1e6, 3: 523.6e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 259.5e6, 3: 523.6e6}
 
 
 def cpu_baseline(cfg, ep, budget_s: float = 12.0):
