@@ -257,15 +257,39 @@ def contention_study(args, cfg, torch, ob) -> int:
         torch.cuda.synchronize()
         return ea0.elapsed_time(ea1), eb0.elapsed_time(eb1)
 
+    def masked_streams(n_attn):
+        """Two streams whose kernels may only run on disjoint sets of compute units: mask bits
+        [0, n_attn) for the scorer, the rest for the other load (hipExtStreamCreateWithCUMask; default
+        priority).  Returns None if the runtime refuses."""
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        out = []
+        for lo, hi in ((0, n_attn), (n_attn, 256)):
+            words = (ctypes.c_uint32 * 8)(*[sum(1 << b for b in range(32) if lo <= 32 * w + b < hi) for w in range(8)])
+            h = ctypes.c_void_p()
+            if hip.hipExtStreamCreateWithCUMask(ctypes.byref(h), 8, words) != 0 or not h.value:
+                return None
+            out.append(torch.cuda.ExternalStream(h.value))
+        return out
+
     rows = []
     n_ep, n_dec = 120, 60
-    for cus in (256, 192, 128):
+    plain = (sa, sb)
+    for cus, masked in ((256, False), (192, False), (128, False), (192, True), (128, True)):
+        if masked:
+            pair = masked_streams(cus)
+            if pair is None:
+                rows.append({"attention_cus": cus, "cu_masks": "refused by the runtime"})
+                continue
+            sa, sb = pair
+        else:
+            sa, sb = plain
         ob.oppo_set_option(ob.OPT_NUM_CUS, cus)
         timed(attn, decode, 40, 20)                      # warm-up
         a_alone, _ = timed(attn, None, n_ep, 0)
         _, d_alone = timed(None, decode, 0, n_dec)
         a_both, d_both = timed(attn, decode, n_ep, n_dec)
-        rows.append({"attention_cus": cus,
+        rows.append({"attention_cus": cus, "cu_masks": bool(masked),
                      "episode_ms_alone": a_alone / n_ep, "episode_ms_colocated": a_both / n_ep,
                      "tflops_alone": flops / (a_alone / n_ep * 1e-3) / 1e12,
                      "tflops_colocated": flops / (a_both / n_ep * 1e-3) / 1e12,
@@ -365,7 +389,7 @@ def main() -> int:
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
-                         "restricted to 256 / 192 / 128 compute units (OPPO_OPT_NUM_CUS)")
+                         "restricted to 256 / 192 / 128 compute units (OPPO_OPT_NUM_CUS), without and with CU masks on the two streams")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
