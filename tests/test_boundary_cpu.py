@@ -290,3 +290,14 @@ def test_planner_balances_whole_tiles_by_exchanging_them(lib):
     for sq in np.unique(items[:, 0]):
         mine = items[items[:, 0] == sq][:, 7]
         assert len(set(mine.tolist())) == len(mine)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message that says so,
+    before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
