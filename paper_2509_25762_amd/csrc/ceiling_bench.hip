@@ -4,7 +4,8 @@
 // per 64-key tile (MFMAs, LDS operand reads, exp2 / convert / row-sum vector work)
 // without global loads and barriers - as the kernel has it (32 query columns per wave,
 // 8 waves) and with 64 columns per wave (4 waves).  Not part of the library; prints a
-// table.  Build-time switches for ablations of the mix loop: see MIX_NO_* below.
+// table, then a probe of whether a wave's vector work overlaps its own MFMAs.
+// Build-time switches for ablations of the mix loop: see MIX_NO_* below.
 //
 //   hipcc --offload-arch=gfx950 -O3 -o ceiling_bench ceiling_bench.hip && ./ceiling_bench
 #include <hip/hip_runtime.h>
@@ -306,6 +307,60 @@ __global__ __launch_bounds__(256) void attention_mix64(const unsigned short* rnd
   if (blockIdx.x == 0 && threadIdx.x == 0) clk[0] = tt1 - tt0, clk[1] = w1 - w0;
 }
 
+// Does a wave's vector work hide under its own MFMAs?  A loop of { MFMA ; NV independent
+// v_fma_f32 } on alternating accumulators, with one and with two waves per SIMD.
+template <int NV>
+__global__ void overlap_probe(float* out, int iters, long long* clk, float c) {
+  bf16x8 a, b;
+  for (int j = 0; j < 8; ++j) {
+    a[j] = (__bf16)(float)((threadIdx.x + j) & 7);
+    b[j] = (__bf16)(float)(j + 1);
+  }
+  f32x16 acc0 = {0}, acc1 = {0};
+  float x[8];
+  for (int j = 0; j < 8; ++j) x[j] = (float)(threadIdx.x + j);
+  __syncthreads();
+  const long long t0 = clock64();
+  for (int it = 0; it < iters; ++it) {
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc0, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      x[v % 8] = __builtin_fmaf(x[v % 8], c, 1.0f);
+      asm volatile("" : "+v"(x[v % 8]));
+    }
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc1, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      x[(v + 4) % 8] = __builtin_fmaf(x[(v + 4) % 8], c, 1.0f);
+      asm volatile("" : "+v"(x[(v + 4) % 8]));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  const long long t1 = clock64();
+  float s = 0;
+  for (int j = 0; j < 16; ++j) s += acc0[j] + acc1[j];
+  for (int j = 0; j < 8; ++j) s += x[j];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  // the slowest wave of workgroup 0 (waves that share a SIMD do not get equal shares)
+  if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) atomicMax((unsigned long long*)clk, (unsigned long long)(t1 - t0));
+}
+
+template <int NV>
+static void run_overlap_probe(float* out, long long* clk, int threads) {
+  const int iters = 20000;
+  for (int r = 0; r < 3; ++r) {
+    CK(hipMemset(clk, 0, 8));
+    hipLaunchKernelGGL(overlap_probe<NV>, dim3(kBlocks), dim3(threads), 0, 0, out, iters, clk, 0.999f);
+  }
+  CK(hipDeviceSynchronize());
+  long long c;
+  CK(hipMemcpy(&c, clk, 8, hipMemcpyDeviceToHost));
+  // cycles one SIMD spends per MFMA slot: a wave's cycles per MFMA, divided by the waves that share the SIMD
+  printf("%d wave(s) per SIMD, %2d v_fma per MFMA: %6.1f cycles per MFMA and SIMD\n", threads / 256, NV,
+         (double)c / iters / 2 / (threads / 256));
+  fflush(stdout);
+}
+
 static unsigned short to_bf16(float f) {
   union { float f; unsigned int u; } cv;
   cv.f = f;
@@ -357,6 +412,13 @@ int main() {
       printf("%-44s %10.0f %12.2f\n", label, flop / (ms * 1e-3) / 1e12, (double)c[0] / ((double)c[1] * 10.0));
       fflush(stdout);
     }
+  }
+  printf("\nown-wave overlap of vector work with MFMAs\n");
+  for (int threads : {256, 512}) {
+    run_overlap_probe<0>(out, clk, threads);
+    run_overlap_probe<4>(out, clk, threads);
+    run_overlap_probe<8>(out, clk, threads);
+    run_overlap_probe<16>(out, clk, threads);
   }
   return 0;
 }
