@@ -69,7 +69,7 @@ def cpu_baseline(cfg, ep, budget_s: float = 12.0):
 
 
 def chunk_sweep(args, cfg, torch, ob) -> int:
-    """The intra-step trade-off in the scorer's own terms (Sec. 3.1; Sec. 4.4, chunk-size ablation):
+    """The intra-step trade-off in the scorer's own terms (Sec. 3.1; Sec. 4.3, impact of streaming degrees):
     small chunks cost GPU time (more passes, more fixed cost per pass), large chunks leave a long last
     pass that starts only when generation has ended and so cannot be hidden behind it."""
     import dataclasses
@@ -202,6 +202,78 @@ def overlap_study(args, cfg, torch, ob) -> int:
                       "sweep": rows, "tuner_pick": picked, "n_gpus": 1, "data": "synthetic",
                       "note": "attention passes measured, everything else from the stated model; response tokens "
                               f"{int(resp_tokens)}, all tokens {int(all_tokens)}"}))
+    return 0
+
+
+def inter_step_study(args, cfg, torch, ob) -> int:
+    """Inter-step overlap in the paper's own quantity (Sec. 3.2, Alg. 1): time to turn a dataset into
+    PPO batches of B sequences when the buffer holds B + Delta, so that an iteration ends with the
+    B-th finisher instead of the slowest sequence and the unfinished ones carry their cached prefix
+    over.  Every pass of the library's scheduler / slot pool / fused attention call is measured
+    (library events, x the model's layer count); generation and the scorer's dense work come from the
+    stated synthetic model (workload.TimingModel); each iteration is one intra-step timeline
+    (oppo_overlap_timeline), iterations follow one another (the PPO update in between is the same
+    for every Delta and left out).  Baseline: Delta = 0 without streaming (generate, then score once)."""
+    import dataclasses as dc
+    from paper_2509_25762_amd.episode import BufferedRun
+    from paper_2509_25762_amd.workload import TimingModel, build_episode, pass_generation_time
+    model = TimingModel()
+    B = cfg.batch
+    n_seq = 4 * B
+    ep = build_episode(dc.replace(cfg, batch=n_seq), threads=min(16, len(os.sched_getaffinity(0))))
+    reps = 3
+    rows = []
+    ob.oppo_profile_enable(True)
+    for delta in (0, 4, 8, 16, 32):
+        run = BufferedRun(ep, B, delta, cfg.chunk)
+        passes = run.passes()
+        pass_ms = np.zeros(len(passes))
+        for r in range(reps + 1):
+            run.reset()
+            k = 0
+            for e in run.events:
+                if e[0] == "acquire":
+                    ob.oppo_pool_acquire(run.pool, e[1], e[2])
+                elif e[0] == "release":
+                    ob.oppo_pool_release(run.pool, e[1])
+                elif e[0] == "pass":
+                    ps = e[1]
+                    ob.oppo_profile_read()
+                    ob.oppo_chunk_step(run.desc, run.cache, ps.cu_q, ps.q, ps.k, ps.v, ps.out, run.workspace)
+                    kms, _ = ob.oppo_profile_read()
+                    if r:
+                        pass_ms[k] += (kms["attn"] + kms["merge"] + kms["append"]) / reps
+                    k += 1
+        n_iter = len(run.removed)
+        tot = {"generation_s": 0.0, "scoring_s": 0.0, "exposed_s": 0.0, "step_s": 0.0, "sequential_s": 0.0}
+        for it in range(n_iter):
+            idx = [k for k, ps in enumerate(passes) if ps.iteration == it]
+            gen = [0.0 if passes[k].kind == ob.PASS_PROMPT else pass_generation_time(passes[k].kv_before, passes[k].q_len, model)
+                   for k in idx]
+            score = [model.layers * pass_ms[k] * 1e-3 + model.dense_s(float(np.sum(passes[k].q_len))) for k in idx]
+            _, _, summ = ob.oppo_overlap_timeline(gen, score)
+            tot["generation_s"] += float(np.sum(gen))
+            tot["scoring_s"] += float(np.sum(score))
+            tot["exposed_s"] += summ["exposed"]
+            tot["step_s"] += summ["step_end"]
+            n_chunk = sum(1 for k in idx if passes[k].kind != ob.PASS_PROMPT)
+            tot["sequential_s"] += float(np.sum(gen)) - max(0, n_chunk - 1) * model.handoff_s + float(np.sum(score))
+        rows.append({"delta": delta, "slots": B + delta, "iterations": n_iter, "passes": len(passes),
+                     "attention_s": float(model.layers * pass_ms.sum() * 1e-3), **tot,
+                     "sequences_per_s": n_seq / tot["step_s"]})
+        del run
+        torch.cuda.empty_cache()
+    ob.oppo_profile_enable(False)
+    base = rows[0]["sequential_s"]
+    for r in rows:
+        r["speedup_vs_sequential"] = base / r["step_s"]
+        r["speedup_vs_streaming_only"] = rows[0]["step_s"] / r["step_s"]
+    print(json.dumps({"metric": "modelled time for a dataset with inter-step overlap vs Delta",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}) lengths, {n_seq} sequences, PPO batch B={B}, "
+                                             f"C={cfg.chunk}, buffer of B + Delta slots"},
+                      "model": dataclasses.asdict(model), "baseline": "Delta = 0, generate then score (sequential_s of the first row)",
+                      "rows": rows, "n_gpus": 1, "data": "synthetic",
+                      "note": "attention passes measured, everything else from the stated model"}))
     return 0
 
 
@@ -387,6 +459,10 @@ def main() -> int:
                     help="intra-step overlap as a timeline: measured attention passes of the scorer (x 32 layers) "
                          "against a stated synthetic model of the generating side, per chunk size 16..2048: "
                          "hidden fraction of the scoring time, step time, speed-up over generate-then-score")
+    ap.add_argument("--inter-step", action="store_true",
+                    help="inter-step overlap as a timeline: 4 x batch sequences turned into PPO batches through a buffer "
+                         "of batch + Delta slots (Alg. 1) for Delta = 0..32; measured scorer passes against the stated "
+                         "synthetic model of the generating side; time per dataset and speed-up over Delta = 0")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -416,6 +492,8 @@ def main() -> int:
         return chunk_sweep(args, cfg, torch, ob)
     if args.overlap:
         return overlap_study(args, cfg, torch, ob)
+    if args.inter_step:
+        return inter_step_study(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))

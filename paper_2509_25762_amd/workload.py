@@ -8,7 +8,7 @@ parity test can be fed from it.
 The lengths stand in for the rollouts of the paper's PPO runs (Sec. 4.1): most
 responses are short and a few are much longer (Sec. 2.2, long-tailed response
 lengths), which is modelled with a clipped log-normal.  Chunk sizes bracket the
-ones the paper discusses (Sec. 3.1: 128/256/512 candidates; Sec. 4.4 sweep).
+ones the paper discusses (Sec. 3.1: 128/256/512 candidates; Sec. 4.3 sweep).
 
 Recipe (fixed so that every run sees the same numbers):
   rng = numpy.random.default_rng(seed)                       (PCG64)
@@ -233,3 +233,16 @@ def generation_times(prompt_len, resp_len, C: int, model: TimingModel) -> List[f
             t += model.decode_step_s(float((P[live] + j).sum()))
         out.append(t)
     return out
+
+
+def pass_generation_time(kv_before, q_len, model: TimingModel) -> float:
+    """Seconds the modelled actor needs to produce one pass's rows: sequence i decodes
+    q_len[i] tokens on top of kv_before[i], all in lockstep, each step reading the
+    weights and the K/V of the sequences still decoding; plus one hand-off."""
+    kvb = np.asarray(kv_before, dtype=np.int64)
+    ql = np.asarray(q_len, dtype=np.int64)
+    t = model.handoff_s
+    for j in range(int(ql.max()) if len(ql) else 0):
+        live = ql > j
+        t += model.decode_step_s(float((kvb[live] + j).sum()))
+    return t
