@@ -1,5 +1,6 @@
 """Generator tests (CPU): seeds reproduce, bounds hold, stragglers forced."""
 import numpy as np
+import pytest
 
 from paper_2509_25762_amd.workload import (CONFIGS, build_episode, draw_lengths, draw_tensor_bits,
                                             f32_to_bf16_bits, step_work)
@@ -67,3 +68,29 @@ def test_step_work_counts_visible_pairs():
     assert w["flops"] == 4.0 * 64 * 4 * (11 + 12 + 1 + 2 + 3)
     assert w["kv_read_bytes"] == (12 + 3) * 4 * 64 * 2 * 2
     assert w["rows"] == 5 and w["active"] == 2
+
+
+def test_timing_model_of_the_generating_side():
+    """The synthetic timing model that stands in for the actor (stated figures, not the method):
+    a decode step reads the weights and every live token's K/V once; a chunk is its steps plus one
+    hand-off; per-chunk and per-pass bookkeeping agree."""
+    from paper_2509_25762_amd.workload import TimingModel, generation_times, pass_generation_time
+    m = TimingModel()
+    assert m.decode_step_s(0) == pytest.approx(m.decode_step_overhead_s + m.weight_bytes / m.decode_bytes_per_s)
+    assert m.decode_step_s(1000) - m.decode_step_s(0) == pytest.approx(1000 * m.kv_bytes_per_token / m.decode_bytes_per_s)
+    assert m.dense_s(10) == pytest.approx(10 * m.dense_flops_per_token / m.dense_flops_per_s)
+    P = np.array([5, 9, 2], dtype=np.int64)
+    R = np.array([7, 3, 0], dtype=np.int64)
+    # by hand: steps j = 0..6; live tokens P_i + j summed over sequences with R_i > j
+    live = [(5 + j) + ((9 + j) if j < 3 else 0) for j in range(7)]
+    step = [m.decode_step_s(x) for x in live]
+    g = generation_times(P, R, 4, m)
+    assert len(g) == 2
+    assert g[0] == pytest.approx(m.handoff_s + sum(step[:4]))
+    assert g[1] == pytest.approx(m.handoff_s + sum(step[4:]))
+    # the same chunks as passes of a schedule: (kv_before, q_len) of the sequences with rows
+    assert pass_generation_time([5, 9], [4, 3], m) == pytest.approx(g[0])
+    assert pass_generation_time([9], [3], m) == pytest.approx(g[1])
+    assert pass_generation_time([], [], m) == pytest.approx(m.handoff_s)
+    # smaller chunks: same decode steps, more hand-offs
+    assert sum(generation_times(P, R, 1, m)) == pytest.approx(sum(g) + 5 * m.handoff_s)
