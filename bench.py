@@ -2,12 +2,20 @@
 """Benchmark of the streamed chunked-prefill path on one MI355X.
 
 One "step" is one streamed episode of the workload: every pass t = 0..T-1 of
-the streaming loop (Alg. 1, generation loop; Sec. 3.1), each pass being
-oppo_kv_append followed by oppo_chunk_prefill_attn over the ragged set of
-unfinished sequences.  Prompts are prefilled once before the timed region
-(reported separately).  Inputs are synthetic and resident in HBM.
+the streaming loop (Alg. 1, generation loop; Sec. 3.1), each pass being one
+oppo_chunk_step (KV append fused into the chunked-prefill attention; with
+--two-call: oppo_kv_append followed by oppo_chunk_prefill_attn) over the ragged
+set of unfinished sequences.  Prompts are prefilled once before the timed
+region (reported separately).  Inputs are synthetic and resident in HBM.
 
-Prints ONE JSON line (see README for the field meanings).
+Prints ONE JSON line: `value` = algorithmic attention FLOPs of the episode per
+second of wall time over the timed episodes (TFLOP/s); `roofline` = the
+attention kernel alone (FLOPs, or bytes on a workload the memory roof binds,
+per second of kernel time measured with HIP events on the launch stream,
+against the chip's published peak; `traffic` = HBM bytes per launch measured
+with rocprofv3 counters); `cpu_baseline` = the float64 oracle timed on a bounded
+sample of the same workload.  Other modes (--deferral, --chunk-sweep, --overlap,
+--inter-step, --contention) print one JSON line of their own.
 """
 from __future__ import annotations
 
