@@ -19,6 +19,10 @@ exactly):
                     iterations (Sec. 3.2): which sequences enter, stream, sit
                     out, leave and carry their cache over, pass by pass;
   * tuner.py      - the periodic search over candidate chunk sizes (Sec. 3.1);
+  * rope.py       - the rotary position embedding of a pass's query and key rows at
+                    their absolute positions (the published definition; the paper is
+                    silent on it), the step before append and attention in the scorer's
+                    layers;
   * overlap.py    - the timeline of intra-step overlap (Sec. 3.1): when the scorer
                     works on which chunk while the actor decodes the next one, and
                     how much scoring time stays exposed at the end of the step.
@@ -38,7 +42,10 @@ recomputed or skipped); the tuner by a hand-worked run and by the argmin
 property over random step times; the overlap timeline by hand-worked cases
 (tests/golden), a tick-by-tick simulation on integer durations and its closed
 forms (a scorer that keeps up exposes only the last chunk; one that never
-idles ends at gen[0] + sum(score)).  No function here is "parity unpinned".
+idles ends at gen[0] + sum(score)); the rotary embedding by a hand-worked row
+(tests/golden), the complex-number form through an independent routine, and its
+defining properties (identity at position 0, additivity, scores that depend on
+relative position only).  No function here is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
@@ -46,10 +53,11 @@ from .schedule import chunk_schedule, num_steps
 from .deferral import simulate as simulate_alg1_buffer, dense_descriptor
 from .tuner import ChunkTunerOracle, run_tuner
 from .overlap import timeline as overlap_timeline, sequential_step
+from .rope import rope_rotate, pass_positions
 
 __all__ = [
     "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
     "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
     "simulate_alg1_buffer", "dense_descriptor", "ChunkTunerOracle", "run_tuner",
-    "overlap_timeline", "sequential_step",
+    "overlap_timeline", "sequential_step", "rope_rotate", "pass_positions",
 ]
