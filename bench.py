@@ -285,6 +285,45 @@ def inter_step_study(args, cfg, torch, ob) -> int:
     return 0
 
 
+def rope_bench(args, cfg, torch, ob) -> int:
+    """The rotary embedding of a pass's rows (oppo_rope), HBM-bound: every q and k row of the
+    workload's first response pass is read and written once.  Timed with events on the launch
+    stream; each launch turns the same rows once more (the values stay finite: a rotation)."""
+    from paper_2509_25762_amd.workload import draw_lengths
+    P, R = draw_lengths(cfg)
+    q_len = np.minimum(cfg.chunk, R).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    rows = int(cu[-1])
+    dev = torch.device("cuda:0")
+    # several copies taken in turn: together larger than the chip's 256 MB last-level cache, so that
+    # every launch finds its rows in HBM
+    ncopy = max(1, args.copies)
+    qs = [torch.randn((rows, cfg.num_q_heads, cfg.head_dim), device=dev, dtype=torch.bfloat16).view(torch.int16) for _ in range(ncopy)]
+    ks = [torch.randn((rows, cfg.num_kv_heads, cfg.head_dim), device=dev, dtype=torch.bfloat16).view(torch.int16) for _ in range(ncopy)]
+    desc = ob.make_desc(cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.softmax_scale)
+    steps, warmup = max(20, args.steps), max(10, args.warmup)
+    for i in range(warmup):
+        ob.oppo_rope(desc, P, cu, qs[i % ncopy], ks[i % ncopy])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        ob.oppo_rope(desc, P, cu, qs[i % ncopy], ks[i % ncopy])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = 2.0 * rows * (cfg.num_q_heads + cfg.num_kv_heads) * cfg.head_dim * 2
+    print(json.dumps({"metric": "rotary embedding of a pass's q and k rows, in place", "value": nbytes / (ms * 1e-3) / 1e9,
+                      "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}), first response pass: {rows} rows x "
+                                             f"({cfg.num_q_heads} + {cfg.num_kv_heads}) heads x {cfg.head_dim}, {ncopy} copies in turn"},
+                      "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                   "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, "traffic": None, "kernel": "rope_kernel",
+                                   "algorithmic_bytes_per_launch": nbytes}}))
+    return 0
+
+
 def contention_study(args, cfg, torch, ob) -> int:
     """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
     colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
@@ -471,6 +510,8 @@ def main() -> int:
                     help="inter-step overlap as a timeline: 4 x batch sequences turned into PPO batches through a buffer "
                          "of batch + Delta slots (Alg. 1) for Delta = 0..32; measured scorer passes against the stated "
                          "synthetic model of the generating side; time per dataset and speed-up over Delta = 0")
+    ap.add_argument("--rope", action="store_true",
+                    help="time oppo_rope (rotary embedding of a pass's q and k rows) on the workload's first response pass")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -502,6 +543,8 @@ def main() -> int:
         return overlap_study(args, cfg, torch, ob)
     if args.inter_step:
         return inter_step_study(args, cfg, torch, ob)
+    if args.rope:
+        return rope_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))

@@ -105,6 +105,30 @@ int oppo_kv_append(const oppo_attn_desc* desc, oppo_kv_cache* cache,
                    const void* k_new, const void* v_new, void* stream);
 
 /*
+ * Rotary position embedding of a pass's rows, in place: the step of the scorer's
+ * attention layers that comes before the append and the attention (the paper is
+ * silent on it; this is the published definition - Su et al., "RoFormer", Sec. 3.2
+ * and 3.4.2 - in the half-split pairing of the Llama / Qwen families the paper
+ * trains, Sec. 4.1).  Row j of sequence i's chunk sits at absolute position
+ * p = kv_before[i] + j; with theta_t = theta_base^(-2 t / D), every pair
+ * (x_t, x_{t + D/2}), t = 0 .. D/2 - 1, of every head of that row turns by
+ * p * theta_t:  x_t' = x_t cos - x_{t+D/2} sin,  x_{t+D/2}' = x_{t+D/2} cos + x_t sin.
+ * Because the angle depends on the absolute position only, keys rotated when their
+ * chunk arrived stay valid in the cache for every later chunk (Sec. 3.1).
+ *   kv_before : HOST int32[batch], tokens of each sequence before this pass.
+ *   cu_q      : HOST int32[batch + 1], prefix sums of the pass's rows per sequence.
+ *   q         : DEVICE bf16 [cu_q[batch]][Hq][D], rotated in place; null: skipped.
+ *   k_new     : DEVICE bf16 [cu_q[batch]][Hkv][D], rotated in place; null: skipped.
+ *   theta_base: > 1 (10000 in the original formulation).
+ * Angles are formed in double precision, the rotation is fp32 with one rounding
+ * to bf16.  The call enqueues on `stream` and returns; the host arrays may be
+ * reused at once.  INVALID for null / malformed host arrays, negative lengths,
+ * positions beyond 2^31, theta_base <= 1; UNSUPPORTED as for the descriptor.
+ */
+int oppo_rope(const oppo_attn_desc* desc, int32_t batch, const int32_t* kv_before, const int32_t* cu_q, void* q,
+              void* k_new, double theta_base, void* stream);
+
+/*
  * Chunked-prefill attention (step 2 above).  cache->kv_len is the length AFTER
  * the chunk was appended.  Row j of sequence i (row cu_q[i]+j of q and out,
  * device bf16 [cu_q[B]][Hq][D]) is the token at absolute position

@@ -30,7 +30,7 @@ OPT_NUM_CUS = 2
 
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
-    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version",
+    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope",
     "oppo_profile_enable", "oppo_profile_read",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
@@ -126,6 +126,8 @@ def load() -> ctypes.CDLL:
     lib.oppo_tuner_destroy.argtypes = [vp]
     lib.oppo_tuner_chunk.argtypes = [vp, ctypes.c_int64, i32p]
     lib.oppo_tuner_report.argtypes = [vp, ctypes.c_int64, ctypes.c_double]
+    lib.oppo_rope.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, i32p, vp, vp, ctypes.c_double, vp]
+    lib.oppo_rope.restype = ctypes.c_int
     lib.oppo_overlap_timeline.argtypes = [ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.oppo_overlap_timeline.restype = ctypes.c_int
     for name in EXPORTS:
@@ -370,6 +372,14 @@ def oppo_tuner_chunk(t: ChunkTuner, step: int) -> int:
 
 def oppo_tuner_report(t: ChunkTuner, step: int, seconds: float) -> None:
     _check(load().oppo_tuner_report(t.handle, step, seconds))
+
+
+def oppo_rope(desc: AttnDesc, kv_before, cu_q, q, k_new, theta_base: float = 10000.0, stream=None) -> None:
+    """Rotates the pass's query rows and new key rows in place (either may be None)."""
+    cu = _i32(cu_q)
+    kvb = _i32(kv_before, cu.shape[0] - 1)
+    _check(load().oppo_rope(ctypes.byref(desc), kvb.shape[0], _i32p(kvb), _i32p(cu), _dev_ptr(q), _dev_ptr(k_new),
+                            float(theta_base), _stream_ptr(stream)))
 
 
 def oppo_overlap_timeline(gen_s, score_s):

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "liboppo_attn.so")
 # stand-alone measurement of the chip's power-limited MFMA rate (not part of the library)
 CEILING_BENCH = os.path.join(HERE, "ceiling_bench")
 
-SOURCES = ["kernels.hip", "api.cpp", "pool.cpp", "sched.cpp"]
+SOURCES = ["kernels.hip", "rope.hip", "api.cpp", "pool.cpp", "sched.cpp"]
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # no NaN ever enters a max/min here (masked scores are -inf): lets the

@@ -572,6 +572,35 @@ int oppo_kv_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32
   return OPPO_OK;
 }
 
+int oppo_rope(const oppo_attn_desc* desc, int32_t batch, const int32_t* kv_before, const int32_t* cu_q, void* q,
+              void* k_new, double theta_base, void* stream) {
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  if (batch < 0) return fail(OPPO_ERR_INVALID, "batch is negative");
+  if (!kv_before && batch > 0) return fail(OPPO_ERR_INVALID, "kv_before is null");
+  rc = check_cu(cu_q, batch, "cu_q");
+  if (rc) return rc;
+  if (!(theta_base > 1.0) || !std::isfinite(theta_base))
+    return fail(OPPO_ERR_INVALID, "theta_base must be finite and greater than 1 (got %g)", theta_base);
+  std::vector<oppo::RopeItem> items;
+  for (int32_t i = 0; i < batch; ++i) {
+    const int32_t ql = cu_q[i + 1] - cu_q[i];
+    if (kv_before[i] < 0) return fail(OPPO_ERR_INVALID, "kv_before[%d]=%d is negative", i, kv_before[i]);
+    if ((int64_t)kv_before[i] + ql > INT32_MAX) return fail(OPPO_ERR_INVALID, "sequence %d: positions exceed 2^31", i);
+    if (ql == 0) continue;
+    oppo::RopeItem it;
+    it.row0 = cu_q[i];
+    it.n_tok = ql;
+    it.pos0 = kv_before[i];
+    items.push_back(it);
+  }
+  if (items.empty() || (!q && !k_new)) return OPPO_OK;
+  int e = oppo::launch_rope(ls, q, k_new, items.data(), (int)items.size(), theta_base, stream);
+  if (e) return fail(OPPO_ERR_HIP, "rope launch failed: %s", oppo::hip_error_string(e));
+  return OPPO_OK;
+}
+
 int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cache, const int32_t* cu_q,
                             const void* q, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   oppo::LayerShape ls;

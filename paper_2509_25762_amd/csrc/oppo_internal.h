@@ -58,6 +58,14 @@ struct AppendItem {
   int32_t n_tok;
 };
 
+// One contiguous run of a pass's rows to rotate: rows [row0, row0 + n_tok) of q / k_new
+// sit at absolute positions pos0, pos0 + 1, ...
+struct RopeItem {
+  int32_t row0;
+  int32_t n_tok;
+  int32_t pos0;
+};
+
 struct LayerShape {
   int32_t Hq, Hkv, G, D;
   int32_t TM;       // tokens per query tile = kTileRows / G
@@ -75,6 +83,9 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
                    const CombineItem* items, int n_items, void* stream);
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
                   const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
+// q / k null: that array is left alone.  (rope.hip)
+int launch_rope(const LayerShape& ls, void* q, void* k, const RopeItem* items, int n_items, double theta_base,
+                void* stream);
 const char* hip_error_string(int err);
 
 // Records the reason of a failing call (thread-local, read by oppo_last_error) and

@@ -301,3 +301,24 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_rope_validation(lib):
+    desc = ob.make_desc(8, 2, 128, 0.1)
+    kvb = np.array([3, 4], np.int32)
+    cu = np.array([0, 2, 5], np.int32)
+    f = lib.oppo_rope
+    p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    assert f(None, 2, p(kvb), p(cu), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), -1, p(kvb), p(cu), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), 2, None, p(cu), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), 2, p(kvb), None, None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), 2, p(kvb), p(np.array([0, 3, 2], np.int32)), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), 2, p(np.array([3, -1], np.int32)), p(cu), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    assert f(ctypes.byref(desc), 2, p(np.array([3, 2 ** 31 - 2], np.int32)), p(cu), None, None, 10000.0, None) == ob.OPPO_ERR_INVALID
+    for bad in (1.0, 0.0, -5.0, float("nan"), float("inf")):
+        assert f(ctypes.byref(desc), 2, p(kvb), p(cu), None, None, bad, None) == ob.OPPO_ERR_INVALID
+    assert "theta_base" in ob.oppo_last_error()
+    # nothing to rotate: no device is touched
+    assert f(ctypes.byref(desc), 2, p(kvb), p(cu), None, None, 10000.0, None) == ob.OPPO_OK
+    assert f(ctypes.byref(desc), 2, p(kvb), p(np.zeros(3, np.int32)), None, None, 10000.0, None) == ob.OPPO_OK

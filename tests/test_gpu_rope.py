@@ -1,0 +1,111 @@
+"""GPU parity of the rotary embedding (oppo_rope) against the float64 oracle, and of the
+layer path rope -> fused append + attention against the oracle's rope -> one-shot prefill.
+
+Tolerance of the rotation itself: the kernel rounds once to bf16 from an fp32 rotation with
+double-precision angles, so |gpu - oracle| <= 2^-8 * |oracle| (half a bf16 ulp at most, plus
+fp32 noise), and all but a handful of elements equal the oracle's value rounded to bf16."""
+import numpy as np
+import pytest
+
+from oracle import bf16_bits_to_f64, full_prefill, pass_positions, rope_rotate
+from paper_2509_25762_amd.workload import CONFIGS, build_episode, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_25762_amd import binding
+    binding.load()
+    return binding, torch
+
+
+def draw_bits(rng, shape):
+    return f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+
+def check_rotation(got_bits, x_bits, pos, base, what):
+    want = rope_rotate(bf16_bits_to_f64(x_bits), pos, base)
+    got = bf16_bits_to_f64(got_bits)
+    err = np.abs(got - want)
+    assert np.isfinite(got).all()
+    assert (err <= 2.0 ** -8 * np.abs(want) * 1.001 + 1e-7).all(), f"{what}: max excess at {np.unravel_index(err.argmax(), err.shape)}"
+    same = got_bits == f32_to_bf16_bits(want.astype(np.float32))
+    assert same.mean() >= 0.999, f"{what}: only {same.mean() * 100:.3f}% equal the rounded oracle value"
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,base", [(8, 2, 128, 10000.0), (6, 2, 64, 10000.0), (4, 4, 64, 500000.0), (16, 1, 128, 1000000.0)])
+def test_rotation_matches_the_oracle_on_a_ragged_pass(gpu, Hq, Hkv, D, base):
+    binding, torch = gpu
+    rng = np.random.default_rng(100 + Hq + D)
+    q_len = np.array([0, 1, 7, 64, 130, 9, 0, 33], dtype=np.int32)
+    kv_before = np.array([17, 0, 60000, 123, 4095, 1, 5, 65536 * 4], dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    n = int(cu[-1])
+    qb, kb = draw_bits(rng, (n, Hq, D)), draw_bits(rng, (n, Hkv, D))
+    pos = pass_positions(kv_before, q_len)
+    desc = binding.make_desc(Hq, Hkv, D, 1.0 / np.sqrt(D))
+    dev = torch.device("cuda:0")
+    # one spare row on either side stays untouched
+    pad = lambda a: np.concatenate([np.full((1,) + a.shape[1:], 0x7FC0, np.uint16), a, np.full((1,) + a.shape[1:], 0x7FC0, np.uint16)])
+    tq = torch.from_numpy(pad(qb).view(np.int16)).to(dev)
+    tk = torch.from_numpy(pad(kb).view(np.int16)).to(dev)
+    binding.oppo_rope(desc, kv_before, cu, tq[1:-1], tk[1:-1], base)
+    torch.cuda.synchronize()
+    gq, gk = tq.cpu().numpy().view(np.uint16), tk.cpu().numpy().view(np.uint16)
+    for g in (gq, gk):
+        assert (g[0] == 0x7FC0).all() and (g[-1] == 0x7FC0).all(), "rows outside the pass were written"
+    check_rotation(gq[1:-1], qb, pos, base, "q")
+    check_rotation(gk[1:-1], kb, pos, base, "k")
+    # either array alone; the other is not touched
+    tq2 = torch.from_numpy(qb.view(np.int16)).to(dev)
+    tk2 = torch.from_numpy(kb.view(np.int16)).to(dev)
+    binding.oppo_rope(desc, kv_before, cu, tq2, None, base)
+    binding.oppo_rope(desc, kv_before, cu, None, tk2, base)
+    torch.cuda.synchronize()
+    assert np.array_equal(tq2.cpu().numpy().view(np.uint16), gq[1:-1])
+    assert np.array_equal(tk2.cpu().numpy().view(np.uint16), gk[1:-1])
+
+
+def test_empty_pass_and_position_zero(gpu):
+    binding, torch = gpu
+    desc = binding.make_desc(4, 2, 64, 0.125)
+    binding.oppo_rope(desc, np.zeros(3, np.int32), np.zeros(4, np.int32), None, None)
+    binding.oppo_rope(desc, np.zeros(0, np.int32), np.zeros(1, np.int32), None, None)
+    rng = np.random.default_rng(5)
+    qb = draw_bits(rng, (1, 4, 64))
+    tq = torch.from_numpy(qb.view(np.int16)).to("cuda:0")
+    binding.oppo_rope(desc, np.array([0], np.int32), np.array([0, 1], np.int32), tq, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(tq.cpu().numpy().view(np.uint16), qb), "position 0 must leave a row bit for bit"
+
+
+def test_layer_path_rope_then_streamed_attention_equals_one_shot(gpu):
+    """Every pass: rotate the chunk's q and k rows at their absolute positions, then the fused
+    append + attention.  The oracle rotates whole sequences once, rounds to bf16 as the device
+    does, and prefills in one shot: streaming with rotated keys in the cache changes nothing
+    (Sec. 3.1)."""
+    binding, torch = gpu
+    from paper_2509_25762_amd import episode
+    cfg = CONFIGS[1]
+    ep = build_episode(cfg, threads=2)
+    base = 10000.0
+    chunks = episode.uniform_chunks(ep.prompt_len, ep.resp_len, 48)
+    se = episode.StreamedEpisode(ep, chunks)
+    for t, st in enumerate(se.steps):
+        binding.oppo_rope(se.desc, st.kv_before, st.cu_q, st.q, st.k, base)
+        se.run_step(t)
+    torch.cuda.synchronize()
+    out = bf16_bits_to_f64(se.scatter_outputs().cpu().numpy().view(np.uint16))
+    ref = np.empty_like(out)
+    for i in range(cfg.batch):
+        lo, hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        pos = np.arange(hi - lo)
+        rq = f32_to_bf16_bits(rope_rotate(bf16_bits_to_f64(ep.q[lo:hi]), pos, base).astype(np.float32))
+        rk = f32_to_bf16_bits(rope_rotate(bf16_bits_to_f64(ep.k[lo:hi]), pos, base).astype(np.float32))
+        ref[lo:hi] = full_prefill(bf16_bits_to_f64(rq), bf16_bits_to_f64(rk), bf16_bits_to_f64(ep.v[lo:hi]), cfg.softmax_scale)
+    err = np.abs(out - ref)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
