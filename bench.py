@@ -324,6 +324,55 @@ def rope_bench(args, cfg, torch, ob) -> int:
     return 0
 
 
+def qkv_epilogue_bench(args, cfg, torch, ob) -> int:
+    """oppo_qkv_rope_append on the workload's first response pass: one pass over the projection's
+    output rows [q | k | v], rotated queries out, rotated keys and values into the cache.  HBM-bound:
+    every byte read once and written once.  Several copies in turn, as for --rope."""
+    from paper_2509_25762_amd.workload import draw_lengths
+    P, R = draw_lengths(cfg)
+    q_len = np.minimum(cfg.chunk, R).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    rows = int(cu[-1])
+    dev = torch.device("cuda:0")
+    heads = cfg.num_q_heads + 2 * cfg.num_kv_heads
+    ncopy = max(1, args.copies)
+    slot_begin = np.concatenate([[0], np.cumsum(P.astype(np.int64) + q_len)])
+    qkvs = [torch.randn((rows, heads, cfg.head_dim), device=dev, dtype=torch.bfloat16).view(torch.int16) for _ in range(ncopy)]
+    q_outs = [torch.empty((rows, cfg.num_q_heads, cfg.head_dim), device=dev, dtype=torch.int16) for _ in range(ncopy)]
+    caches = []
+    for _ in range(ncopy):
+        ck = torch.zeros((int(slot_begin[-1]), cfg.num_kv_heads, cfg.head_dim), device=dev, dtype=torch.int16)
+        caches.append(ob.KVCache(ck, torch.zeros_like(ck), slot_begin, P))
+    desc = ob.make_desc(cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.softmax_scale)
+    steps, warmup = max(20, args.steps), max(10, args.warmup)
+
+    def call(i):
+        c = caches[i % ncopy]
+        c.kv_len[:] = P                        # the same pass again
+        ob.oppo_qkv_rope_append(desc, c, cu, qkvs[i % ncopy], q_outs[i % ncopy])
+
+    for i in range(warmup):
+        call(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        call(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = 2.0 * rows * heads * cfg.head_dim * 2
+    print(json.dumps({"metric": "QKV-projection epilogue: rotary embedding + cache write in one pass", "value": nbytes / (ms * 1e-3) / 1e9,
+                      "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}), first response pass: {rows} rows x "
+                                             f"({cfg.num_q_heads} + 2 x {cfg.num_kv_heads}) heads x {cfg.head_dim}, {ncopy} copies in turn"},
+                      "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                   "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, "traffic": None,
+                                   "kernel": "qkv_rope_append_kernel", "algorithmic_bytes_per_launch": nbytes}}))
+    return 0
+
+
 def contention_study(args, cfg, torch, ob) -> int:
     """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
     colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
@@ -512,6 +561,9 @@ def main() -> int:
                          "synthetic model of the generating side; time per dataset and speed-up over Delta = 0")
     ap.add_argument("--rope", action="store_true",
                     help="time oppo_rope (rotary embedding of a pass's q and k rows) on the workload's first response pass")
+    ap.add_argument("--qkv-epilogue", action="store_true",
+                    help="time oppo_qkv_rope_append (rotary embedding + cache write as one pass over the QKV projection's "
+                         "output) on the workload's first response pass")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -545,6 +597,8 @@ def main() -> int:
         return inter_step_study(args, cfg, torch, ob)
     if args.rope:
         return rope_bench(args, cfg, torch, ob)
+    if args.qkv_epilogue:
+        return qkv_epilogue_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))

@@ -129,6 +129,25 @@ int oppo_rope(const oppo_attn_desc* desc, int32_t batch, const int32_t* kv_befor
               void* k_new, double theta_base, void* stream);
 
 /*
+ * The rotation above as the epilogue of the layer's fused QKV projection, in one
+ * pass over the projection's output: row r of `qkv` holds the Hq query heads, then
+ * the Hkv key heads, then the Hkv value heads of one new token.  For row j of
+ * sequence i (position p = kv_len[i] + j) the call writes the rotated queries to
+ * q_out, the rotated keys and the unchanged values into the sequence's cache slab at
+ * slot kv_len[i] + j, and then advances kv_len like oppo_kv_append does; what
+ * follows is oppo_chunk_prefill_attn on q_out.  Compared with rotating in place and
+ * appending, every byte of the projection's output is read once and written once.
+ *   qkv   : DEVICE bf16 [cu_q[batch]][Hq + 2 Hkv][D], read only.
+ *   q_out : DEVICE bf16 [cu_q[batch]][Hq][D].
+ *   cache : as for oppo_kv_append (HOST length arrays, DEVICE slabs).
+ * Values are copied bit for bit; queries and keys as for oppo_rope.  Errors as for
+ * oppo_kv_append (a failed call writes nothing and leaves the lengths untouched),
+ * and INVALID for theta_base <= 1.
+ */
+int oppo_qkv_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q, const void* qkv,
+                         void* q_out, double theta_base, void* stream);
+
+/*
  * Chunked-prefill attention (step 2 above).  cache->kv_len is the length AFTER
  * the chunk was appended.  Row j of sequence i (row cu_q[i]+j of q and out,
  * device bf16 [cu_q[B]][Hq][D]) is the token at absolute position

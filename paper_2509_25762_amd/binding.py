@@ -30,7 +30,7 @@ OPT_NUM_CUS = 2
 
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
-    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope",
+    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append",
     "oppo_profile_enable", "oppo_profile_read",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
@@ -83,6 +83,9 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_schedule.restype = ctypes.c_int
     lib.oppo_kv_append.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp]
     lib.oppo_kv_append.restype = ctypes.c_int
+    lib.oppo_qkv_rope_append.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp,
+                                         ctypes.c_double, vp]
+    lib.oppo_qkv_rope_append.restype = ctypes.c_int
     lib.oppo_chunk_prefill_attn.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp,
                                             vp, ctypes.c_size_t, vp]
     lib.oppo_chunk_prefill_attn.restype = ctypes.c_int
@@ -439,6 +442,13 @@ def oppo_kv_append(desc: AttnDesc, cache: KVCache, cu_q, k_new, v_new, stream=No
     cu = _i32(cu_q, cache.batch + 1)
     _check(load().oppo_kv_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(k_new),
                                  _dev_ptr(v_new), _stream_ptr(stream)))
+
+
+def oppo_qkv_rope_append(desc: AttnDesc, cache: KVCache, cu_q, qkv, q_out, theta_base: float = 10000.0, stream=None) -> None:
+    """Epilogue of a fused QKV projection: rotated queries to q_out, rotated keys and values into the cache."""
+    cu = _i32(cu_q, cache.batch + 1)
+    _check(load().oppo_qkv_rope_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(qkv),
+                                       _dev_ptr(q_out), float(theta_base), _stream_ptr(stream)))
 
 
 def oppo_chunk_prefill_attn(desc: AttnDesc, cache: KVCache, cu_q, q, out, workspace=None, stream=None) -> None:

@@ -601,6 +601,54 @@ int oppo_rope(const oppo_attn_desc* desc, int32_t batch, const int32_t* kv_befor
   return OPPO_OK;
 }
 
+int oppo_qkv_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q, const void* qkv,
+                         void* q_out, double theta_base, void* stream) {
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  if (!cache) return fail(OPPO_ERR_INVALID, "cache is null");
+  if (cache->batch < 0) return fail(OPPO_ERR_INVALID, "cache->batch is negative");
+  if (!cache->slot_begin || !cache->kv_len) return fail(OPPO_ERR_INVALID, "cache length arrays are null");
+  const int32_t B = cache->batch;
+  rc = check_cu(cu_q, B, "cu_q");
+  if (rc) return rc;
+  if (!(theta_base > 1.0) || !std::isfinite(theta_base))
+    return fail(OPPO_ERR_INVALID, "theta_base must be finite and greater than 1 (got %g)", theta_base);
+  if (cache->slot_begin[0] < 0) return fail(OPPO_ERR_INVALID, "slot_begin[0] is negative");
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t cap = cache->slot_begin[i + 1] - cache->slot_begin[i];
+    if (cap < 0) return fail(OPPO_ERR_INVALID, "slot_begin decreases at %d", i);
+    if (cache->kv_len[i] < 0 || cache->kv_len[i] > cap)
+      return fail(OPPO_ERR_INVALID, "kv_len[%d]=%d outside its slab of %lld slots", i, cache->kv_len[i], (long long)cap);
+  }
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t cap = cache->slot_begin[i + 1] - cache->slot_begin[i];
+    const int64_t ql = cu_q[i + 1] - cu_q[i];
+    if ((int64_t)cache->kv_len[i] + ql > cap)
+      return fail(OPPO_ERR_CAPACITY, "sequence %d: %d cached + %lld new tokens exceed %lld slots", i,
+                  cache->kv_len[i], (long long)ql, (long long)cap);
+  }
+  if (cu_q[B] == 0) return OPPO_OK;
+  if (!cache->k || !cache->v || !qkv || !q_out) return fail(OPPO_ERR_INVALID, "null device pointer");
+  std::vector<oppo::QkvItem> items;
+  for (int32_t i = 0; i < B; ++i) {
+    const int32_t ql = cu_q[i + 1] - cu_q[i];
+    if (ql == 0) continue;
+    oppo::QkvItem it;
+    it.dst_row = cache->slot_begin[i] + cache->kv_len[i];
+    it.src_row = cu_q[i];
+    it.n_tok = ql;
+    it.pos0 = cache->kv_len[i];
+    it.pad_ = 0;
+    items.push_back(it);
+  }
+  int e = oppo::launch_qkv_rope_append(ls, qkv, q_out, cache->k, cache->v, items.data(), (int)items.size(), theta_base,
+                                       stream);
+  if (e) return fail(OPPO_ERR_HIP, "qkv epilogue launch failed: %s", oppo::hip_error_string(e));
+  for (int32_t i = 0; i < B; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
+  return OPPO_OK;
+}
+
 int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cache, const int32_t* cu_q,
                             const void* q, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   oppo::LayerShape ls;

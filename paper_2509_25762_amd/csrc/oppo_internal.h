@@ -66,6 +66,16 @@ struct RopeItem {
   int32_t pos0;
 };
 
+// One sequence's rows of a fused QKV projection output: rows [src_row, src_row + n_tok)
+// at positions pos0, pos0 + 1, ...; keys and values go to cache rows dst_row, dst_row + 1, ...
+struct QkvItem {
+  int64_t dst_row;
+  int32_t src_row;
+  int32_t n_tok;
+  int32_t pos0;
+  int32_t pad_;
+};
+
 struct LayerShape {
   int32_t Hq, Hkv, G, D;
   int32_t TM;       // tokens per query tile = kTileRows / G
@@ -86,6 +96,8 @@ int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void
 // q / k null: that array is left alone.  (rope.hip)
 int launch_rope(const LayerShape& ls, void* q, void* k, const RopeItem* items, int n_items, double theta_base,
                 void* stream);
+int launch_qkv_rope_append(const LayerShape& ls, const void* qkv, void* q_out, void* cache_k, void* cache_v,
+                           const QkvItem* items, int n_items, double theta_base, void* stream);
 const char* hip_error_string(int err);
 
 // Records the reason of a failing call (thread-local, read by oppo_last_error) and

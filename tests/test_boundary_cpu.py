@@ -322,3 +322,24 @@ def test_rope_validation(lib):
     # nothing to rotate: no device is touched
     assert f(ctypes.byref(desc), 2, p(kvb), p(cu), None, None, 10000.0, None) == ob.OPPO_OK
     assert f(ctypes.byref(desc), 2, p(kvb), p(np.zeros(3, np.int32)), None, None, 10000.0, None) == ob.OPPO_OK
+
+
+def test_qkv_epilogue_validation_leaves_lengths_untouched(lib):
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 0])
+    cases = [([0, 3, 6], 10000.0, ob.OPPO_ERR_CAPACITY),   # 6 + 3 > 8
+             ([1, 3, 6], 10000.0, ob.OPPO_ERR_INVALID),    # cu_q[0] != 0
+             ([0, 3, 2], 10000.0, ob.OPPO_ERR_INVALID),    # decreasing
+             ([0, 1, 2], 1.0, ob.OPPO_ERR_INVALID),        # theta_base must exceed 1
+             ([0, 1, 2], float("nan"), ob.OPPO_ERR_INVALID)]
+    for cu, base, code in cases:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_qkv_rope_append(desc, cache, cu, 0x3000, 0x4000, base, stream=0)
+        assert e.value.code == code
+        assert cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:               # rows but no device arrays
+        ob.oppo_qkv_rope_append(desc, cache, [0, 1, 2], None, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID and cache.kv_len.tolist() == [6, 0]
+    # nobody has rows: legal, no device needed
+    ob.oppo_qkv_rope_append(desc, cache, [0, 0, 0], None, None, stream=0)
+    assert cache.kv_len.tolist() == [6, 0]

@@ -109,3 +109,70 @@ def test_layer_path_rope_then_streamed_attention_equals_one_shot(gpu):
         ref[lo:hi] = full_prefill(bf16_bits_to_f64(rq), bf16_bits_to_f64(rk), bf16_bits_to_f64(ep.v[lo:hi]), cfg.softmax_scale)
     err = np.abs(out - ref)
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+
+
+def test_qkv_epilogue_writes_rotated_queries_and_the_cache(gpu):
+    """oppo_qkv_rope_append on a ragged pass over a partly filled cache: queries and keys against
+    the oracle's rotation, values bit for bit, every other cache slot and row untouched, lengths
+    advanced."""
+    binding, torch = gpu
+    rng = np.random.default_rng(77)
+    Hq, Hkv, D, base = 8, 2, 128, 10000.0
+    q_len = np.array([5, 0, 70, 1, 9], dtype=np.int32)
+    kv_before = np.array([0, 12, 300, 4096, 63], dtype=np.int32)
+    cap = kv_before + q_len + 3
+    slot_begin = np.concatenate([[0], np.cumsum(cap)]).astype(np.int64)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    n = int(cu[-1])
+    qkv = draw_bits(rng, (n, Hq + 2 * Hkv, D))
+    dev = torch.device("cuda:0")
+    ck = torch.full((int(slot_begin[-1]), Hkv, D), -1, dtype=torch.int16, device=dev)
+    cv = torch.full_like(ck, -1)
+    cache = binding.KVCache(ck, cv, slot_begin, kv_before.copy())
+    desc = binding.make_desc(Hq, Hkv, D, 1.0 / np.sqrt(D))
+    q_out = torch.full((n, Hq, D), -1, dtype=torch.int16, device=dev)
+    binding.oppo_qkv_rope_append(desc, cache, cu, torch.from_numpy(qkv.view(np.int16)).to(dev), q_out, base)
+    torch.cuda.synchronize()
+    assert cache.kv_len.tolist() == (kv_before + q_len).tolist()
+    pos = pass_positions(kv_before, q_len)
+    check_rotation(q_out.cpu().numpy().view(np.uint16), qkv[:, :Hq], pos, base, "q")
+    gk, gv = ck.cpu().numpy().view(np.uint16), cv.cpu().numpy().view(np.uint16)
+    written = np.zeros(int(slot_begin[-1]), dtype=bool)
+    for i in range(len(q_len)):
+        lo = int(slot_begin[i]) + int(kv_before[i])
+        rows = slice(int(cu[i]), int(cu[i + 1]))
+        written[lo:lo + int(q_len[i])] = True
+        if q_len[i]:
+            check_rotation(gk[lo:lo + int(q_len[i])], qkv[rows, Hq:Hq + Hkv], pos[rows], base, f"k of sequence {i}")
+            assert np.array_equal(gv[lo:lo + int(q_len[i])], qkv[rows, Hq + Hkv:]), f"v of sequence {i}"
+    assert (gk[~written] == 0xFFFF).all() and (gv[~written] == 0xFFFF).all(), "slots outside the pass were written"
+
+
+def test_layer_path_qkv_epilogue_then_attention_equals_one_shot(gpu):
+    """Every pass: the projection's output rows go through oppo_qkv_rope_append, then
+    oppo_chunk_prefill_attn reads the rotated queries and the cache.  Same reference as for the
+    in-place rotation: rotate whole sequences, round to bf16, prefill in one shot."""
+    binding, torch = gpu
+    from paper_2509_25762_amd import episode
+    cfg = CONFIGS[1]
+    ep = build_episode(cfg, threads=2)
+    base = 10000.0
+    chunks = episode.uniform_chunks(ep.prompt_len, ep.resp_len, 40)
+    se = episode.StreamedEpisode(ep, chunks)
+    se.reset(0)
+    for st in se.steps:
+        qkv = torch.cat([st.q, st.k, st.v], dim=1).contiguous()
+        q_rot = torch.empty_like(st.q)
+        binding.oppo_qkv_rope_append(se.desc, se.cache, st.cu_q, qkv, q_rot, base)
+        binding.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, q_rot, st.out, se.workspace)
+    torch.cuda.synchronize()
+    out = bf16_bits_to_f64(se.scatter_outputs().cpu().numpy().view(np.uint16))
+    ref = np.empty_like(out)
+    for i in range(cfg.batch):
+        lo, hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        pos = np.arange(hi - lo)
+        rq = f32_to_bf16_bits(rope_rotate(bf16_bits_to_f64(ep.q[lo:hi]), pos, base).astype(np.float32))
+        rk = f32_to_bf16_bits(rope_rotate(bf16_bits_to_f64(ep.k[lo:hi]), pos, base).astype(np.float32))
+        ref[lo:hi] = full_prefill(bf16_bits_to_f64(rq), bf16_bits_to_f64(rk), bf16_bits_to_f64(ep.v[lo:hi]), cfg.softmax_scale)
+    err = np.abs(out - ref)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
