@@ -373,6 +373,67 @@ def qkv_epilogue_bench(args, cfg, torch, ob) -> int:
     return 0
 
 
+def layer_path_bench(args, cfg, torch, ob) -> int:
+    """The attention side of one scorer layer over the streamed episode, two ways:
+      A  oppo_rope in place on the chunk's q and k rows, then oppo_chunk_step (append fused into attention);
+      B  oppo_qkv_rope_append over the projection's output rows [q | k | v] (rotated keys and values straight
+         into the cache), then oppo_chunk_prefill_attn.
+    Both give the same outputs up to the tolerance (same rotated values, same attention); timed like the
+    main benchmark (prompts prefilled before the timed region, cache copies taken in turn)."""
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import build_episode, episode_work
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
+    T = len(chunks) - 1
+    copies = [StreamedEpisode(ep, chunks) for _ in range(max(1, args.copies))]
+    work = episode_work(cfg, [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
+    flops = sum(w["flops"] for w in work)
+    for se in copies:
+        se.reset(0)
+        se.run_step(0)
+        # inputs of path B: the projection's output rows, and a place for the rotated queries; path A
+        # rotates q and k in place, so it works on copies of its own (rotated again every episode:
+        # the values stay finite, and the timing does not depend on them)
+        se.qkv = [torch.cat([st.q, st.k, st.v], dim=1).contiguous() for st in se.steps]
+        se.q_rot = [torch.empty_like(st.q) for st in se.steps]
+        se.qa = [st.q.clone() for st in se.steps]
+        se.ka = [st.k.clone() for st in se.steps]
+
+    def path_a(se):
+        se.reset(1)
+        for t in range(1, T + 1):
+            st = se.steps[t]
+            ob.oppo_rope(se.desc, st.kv_before, st.cu_q, se.qa[t], se.ka[t])
+            ob.oppo_chunk_step(se.desc, se.cache, st.cu_q, se.qa[t], se.ka[t], st.v, st.out, se.workspace)
+
+    def path_b(se):
+        se.reset(1)
+        for t in range(1, T + 1):
+            st = se.steps[t]
+            ob.oppo_qkv_rope_append(se.desc, se.cache, st.cu_q, se.qkv[t], se.q_rot[t])
+            ob.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, se.q_rot[t], st.out, se.workspace)
+
+    res = {}
+    for name, fn in (("rope_in_place_then_chunk_step", path_a), ("qkv_epilogue_then_attention", path_b)):
+        for w in range(args.warmup):
+            fn(copies[w % len(copies)])
+        torch.cuda.synchronize()
+        gc.collect()
+        gc.disable()
+        t0 = time.perf_counter()
+        for s_ in range(args.steps):
+            fn(copies[s_ % len(copies)])
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        gc.enable()
+        res[name] = {"ms_per_episode": ms, "attention_tflops": flops / (ms * 1e-3) / 1e12}
+    print(json.dumps({"metric": "attention side of one scorer layer over the streamed episode", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}): B={cfg.batch}, C={cfg.chunk}, {T} passes per episode"},
+                      "paths": res}))
+    return 0
+
+
 def contention_study(args, cfg, torch, ob) -> int:
     """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
     colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
@@ -564,6 +625,9 @@ def main() -> int:
     ap.add_argument("--qkv-epilogue", action="store_true",
                     help="time oppo_qkv_rope_append (rotary embedding + cache write as one pass over the QKV projection's "
                          "output) on the workload's first response pass")
+    ap.add_argument("--layer-path", action="store_true",
+                    help="the streamed episode with the rotary embedding included, two ways: oppo_rope + oppo_chunk_step, "
+                         "and oppo_qkv_rope_append + oppo_chunk_prefill_attn")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -599,6 +663,8 @@ def main() -> int:
         return rope_bench(args, cfg, torch, ob)
     if args.qkv_epilogue:
         return qkv_epilogue_bench(args, cfg, torch, ob)
+    if args.layer_path:
+        return layer_path_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
