@@ -434,6 +434,50 @@ def layer_path_bench(args, cfg, torch, ob) -> int:
     return 0
 
 
+def thin_pass_bench(args, cfg, torch, ob) -> int:
+    """Passes with very few new rows per sequence on long contexts (the last chunk of a response,
+    a one-token pass for the final score): the query tile has 1 or 16 tokens x G heads, so most of
+    the workgroup's waves have no rows and only move key tiles; the pass is bound by reading K and V.
+    Uniform batches with the workload's head shape; K/V of all sequences exceed the last-level cache."""
+    dev = torch.device("cuda:0")
+    Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+    desc = ob.make_desc(Hq, Hkv, D, cfg.softmax_scale)
+    rows = []
+    for B, kv_before, q_len in ((64, 4095, 1), (256, 2047, 1), (64, 16383, 1), (64, 4080, 16), (64, 16368, 16)):
+        cap = kv_before + q_len
+        slot_begin = np.arange(B + 1, dtype=np.int64) * cap
+        ck = torch.randn((B * cap, Hkv, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        cv = torch.randn((B * cap, Hkv, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        q = torch.randn((B * q_len, Hq, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        out = torch.empty_like(q)
+        cache = ob.KVCache(ck, cv, slot_begin, np.full(B, cap, dtype=np.int32))
+        cu = (np.arange(B + 1) * q_len).astype(np.int32)
+        ws = torch.empty(ob.oppo_workspace_bytes(desc, B, B * q_len), dtype=torch.uint8, device=dev)
+        steps, warmup = max(50, args.steps), max(20, args.warmup)
+        for _ in range(warmup):
+            ob.oppo_chunk_prefill_attn(desc, cache, cu, q, out, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        gc.collect()
+        gc.disable()
+        e0.record()
+        for _ in range(steps):
+            ob.oppo_chunk_prefill_attn(desc, cache, cu, q, out, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        gc.enable()
+        ms = e0.elapsed_time(e1) / steps
+        kv_bytes = 2.0 * B * cap * Hkv * D * 2          # every key and value row of every sequence, once
+        rows.append({"batch": B, "kv_before": kv_before, "q_len": q_len, "ms": ms, "kv_GBps": kv_bytes / (ms * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": kv_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS})
+        del ck, cv, q, out, ws
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "thin passes: K/V read rate of oppo_chunk_prefill_attn with 1 or 16 new rows per sequence",
+                      "unit": "GB/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"uniform batches, Hq/Hkv/D={Hq}/{Hkv}/{D}"}, "rows": rows}))
+    return 0
+
+
 def contention_study(args, cfg, torch, ob) -> int:
     """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
     colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
@@ -628,6 +672,8 @@ def main() -> int:
     ap.add_argument("--layer-path", action="store_true",
                     help="the streamed episode with the rotary embedding included, two ways: oppo_rope + oppo_chunk_step, "
                          "and oppo_qkv_rope_append + oppo_chunk_prefill_attn")
+    ap.add_argument("--thin-pass", action="store_true",
+                    help="attention passes with 1 or 16 new rows per sequence on contexts of 2K-16K tokens: K/V read rate")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -665,6 +711,8 @@ def main() -> int:
         return qkv_epilogue_bench(args, cfg, torch, ob)
     if args.layer_path:
         return layer_path_bench(args, cfg, torch, ob)
+    if args.thin_pass:
+        return thin_pass_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
