@@ -478,6 +478,53 @@ def thin_pass_bench(args, cfg, torch, ob) -> int:
     return 0
 
 
+def steady_bench(args, cfg, torch, ob) -> int:
+    """The attention call on uniform batches with long contexts (no raggedness, whole tiles, every
+    queue equally long): the kernel's steady state, to set beside the stand-alone instruction-mix
+    loop of ceiling_bench.  One chunk of the workload's size C on top of 8K - C and 1K - C cached tokens."""
+    from paper_2509_25762_amd.workload import step_work
+    dev = torch.device("cuda:0")
+    Hq, Hkv, D, C = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.chunk
+    desc = ob.make_desc(Hq, Hkv, D, cfg.softmax_scale)
+    rows = []
+    for B, total in ((64, 8192), (64, 1024)):
+        kv_before, q_len = max(total, 2 * C) - C, C
+        cap = kv_before + q_len
+        slot_begin = np.arange(B + 1, dtype=np.int64) * cap
+        ck = torch.randn((B * cap, Hkv, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        cv = torch.randn((B * cap, Hkv, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        q = torch.randn((B * q_len, Hq, D), device=dev, dtype=torch.bfloat16).view(torch.int16)
+        out = torch.empty_like(q)
+        cache = ob.KVCache(ck, cv, slot_begin, np.full(B, cap, dtype=np.int32))
+        cu = (np.arange(B + 1) * q_len).astype(np.int32)
+        ws = torch.empty(ob.oppo_workspace_bytes(desc, B, B * q_len), dtype=torch.uint8, device=dev)
+        steps, warmup = max(10, args.steps // 4), max(20, args.warmup)
+        for _ in range(warmup):
+            ob.oppo_chunk_prefill_attn(desc, cache, cu, q, out, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        gc.collect()
+        gc.disable()
+        e0.record()
+        for _ in range(steps):
+            ob.oppo_chunk_prefill_attn(desc, cache, cu, q, out, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        gc.enable()
+        ms = e0.elapsed_time(e1) / steps
+        w = step_work(cfg, np.full(B, kv_before), np.full(B, q_len))
+        rows.append({"batch": B, "kv_before": kv_before, "q_len": q_len, "ms": ms, "tflops": w["flops"] / (ms * 1e-3) / 1e12,
+                     "frac_of_mfma_peak": w["flops"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "kv_GBps": w["kv_read_bytes"] / (ms * 1e-3) / 1e9})
+        del ck, cv, q, out, ws
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "steady state of oppo_chunk_prefill_attn on uniform batches", "unit": "TFLOP/s", "n_gpus": 1,
+                      "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"uniform batches, Hq/Hkv/D={Hq}/{Hkv}/{D}, one chunk of {C} rows per sequence"},
+                      "rows": rows}))
+    return 0
+
+
 def contention_study(args, cfg, torch, ob) -> int:
     """The scorer's chunked prefill next to a generation-like load on the same GPU (Sec. 3.1: with
     colocated models small chunks risk contention).  The attention kernel runs one persistent workgroup
@@ -674,6 +721,9 @@ def main() -> int:
                          "and oppo_qkv_rope_append + oppo_chunk_prefill_attn")
     ap.add_argument("--thin-pass", action="store_true",
                     help="attention passes with 1 or 16 new rows per sequence on contexts of 2K-16K tokens: K/V read rate")
+    ap.add_argument("--steady", action="store_true",
+                    help="the attention call on uniform batches (64 sequences, one chunk on top of 8K and 1K contexts): "
+                         "the kernel's steady state")
     ap.add_argument("--contention", action="store_true",
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
@@ -713,6 +763,8 @@ def main() -> int:
         return layer_path_bench(args, cfg, torch, ob)
     if args.thin_pass:
         return thin_pass_bench(args, cfg, torch, ob)
+    if args.steady:
+        return steady_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
