@@ -80,7 +80,6 @@ def chunk_sweep(args, cfg, torch, ob) -> int:
     """The intra-step trade-off in the scorer's own terms (Sec. 3.1; Sec. 4.3, impact of streaming degrees):
     small chunks cost GPU time (more passes, more fixed cost per pass), large chunks leave a long last
     pass that starts only when generation has ended and so cannot be hidden behind it."""
-    import dataclasses
     from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
     from paper_2509_25762_amd.workload import build_episode, episode_work
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
@@ -222,13 +221,13 @@ def inter_step_study(args, cfg, torch, ob) -> int:
     stated synthetic model (workload.TimingModel); each iteration is one intra-step timeline
     (oppo_overlap_timeline), iterations follow one another (the PPO update in between is the same
     for every Delta and left out).  Baseline: Delta = 0 without streaming (generate, then score once)."""
-    import dataclasses as dc
+
     from paper_2509_25762_amd.episode import BufferedRun
     from paper_2509_25762_amd.workload import TimingModel, build_episode, pass_generation_time
     model = TimingModel()
     B = cfg.batch
     n_seq = 4 * B
-    ep = build_episode(dc.replace(cfg, batch=n_seq), threads=min(16, len(os.sched_getaffinity(0))))
+    ep = build_episode(dataclasses.replace(cfg, batch=n_seq), threads=min(16, len(os.sched_getaffinity(0))))
     reps = 3
     rows = []
     ob.oppo_profile_enable(True)
@@ -627,7 +626,6 @@ def contention_study(args, cfg, torch, ob) -> int:
 
 def deferral_bench(args, cfg, torch, ob) -> int:
     """Alg. 1 with B + Delta slots over a dataset of 2 x batch sequences (see --deferral)."""
-    import dataclasses
     from paper_2509_25762_amd.episode import BufferedRun
     from paper_2509_25762_amd.workload import build_episode, episode_work
     delta = args.deferral
