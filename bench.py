@@ -221,7 +221,6 @@ def inter_step_study(args, cfg, torch, ob) -> int:
     stated synthetic model (workload.TimingModel); each iteration is one intra-step timeline
     (oppo_overlap_timeline), iterations follow one another (the PPO update in between is the same
     for every Delta and left out).  Baseline: Delta = 0 without streaming (generate, then score once)."""
-
     from paper_2509_25762_amd.episode import BufferedRun
     from paper_2509_25762_amd.workload import TimingModel, build_episode, pass_generation_time
     model = TimingModel()
