@@ -2,8 +2,9 @@
 layer path rope -> fused append + attention against the oracle's rope -> one-shot prefill.
 
 Tolerance of the rotation itself: the kernel rounds once to bf16 from an fp32 rotation with
-double-precision angles, so |gpu - oracle| <= 2^-8 * |oracle| (half a bf16 ulp at most, plus
-fp32 noise), and all but a handful of elements equal the oracle's value rounded to bf16."""
+double-precision angles, so |gpu - oracle| <= 2^-8 * |oracle| (half a bf16 ulp at most) plus
+2^-22 * (|x_t| + |x_{t+D/2}|) for the fp32 rounding of the two products (what is left when
+they cancel), and all but a handful of elements equal the oracle's value rounded to bf16."""
 import numpy as np
 import pytest
 
@@ -28,13 +29,20 @@ def draw_bits(rng, shape):
 
 
 def check_rotation(got_bits, x_bits, pos, base, what):
-    want = rope_rotate(bf16_bits_to_f64(x_bits), pos, base)
+    x = bf16_bits_to_f64(x_bits)
+    want = rope_rotate(x, pos, base)
     got = bf16_bits_to_f64(got_bits)
     err = np.abs(got - want)
     assert np.isfinite(got).all()
-    assert (err <= 2.0 ** -8 * np.abs(want) * 1.001 + 1e-7).all(), f"{what}: max excess at {np.unravel_index(err.argmax(), err.shape)}"
-    same = got_bits == f32_to_bf16_bits(want.astype(np.float32))
-    assert same.mean() >= 0.999, f"{what}: only {same.mean() * 100:.3f}% equal the rounded oracle value"
+    # half a bf16 ulp of the result, plus the fp32 rounding of the two products it is the
+    # difference (or sum) of - which is what remains when they cancel
+    half = x.shape[-1] // 2
+    pair = np.abs(x[..., :half]) + np.abs(x[..., half:])
+    bound = 2.0 ** -8 * np.abs(want) * 1.001 + 2.0 ** -22 * np.concatenate([pair, pair], axis=-1) + 1e-30
+    assert (err <= bound).all(), f"{what}: max excess at {np.unravel_index((err - bound).argmax(), err.shape)}"
+    # fp32 noise moves a result across a bf16 rounding boundary about once in 10^4 elements
+    differ = int((got_bits != f32_to_bf16_bits(want.astype(np.float32))).sum())
+    assert differ <= max(2, got_bits.size // 1000), f"{what}: {differ} of {got_bits.size} differ from the rounded oracle value"
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,base", [(8, 2, 128, 10000.0), (6, 2, 64, 10000.0), (4, 4, 64, 500000.0), (16, 1, 128, 1000000.0)])
