@@ -28,6 +28,7 @@ import sys
 import time
 
 import numpy as np
+from typing import List
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -39,6 +40,65 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # scaled by what the same counters read for the append kernel (a plain copy of known
 # size); see profiles/attn_fwd_kernel_config2.md and profiles/attn_fwd_kernel_config3_traffic.md.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 259.5e6, 3: 523.6e6}
+
+
+@dataclasses.dataclass(frozen=True)
+class TimingModel:
+    """Synthetic timing of what surrounds the measured attention passes: the generating
+    side (actor) and the dense part of the scorer's layers.  Stated figures, not
+    measurements - they stand in for the 8B-class models of the paper's runs (Sec. 4.1)
+    on one accelerator each, and only give the measured attention time something to be
+    hidden behind (Sec. 3.1):
+      * a decode step of the actor is bound by memory traffic: all weights plus the
+        K/V of every live token are read once per generated token;
+      * every chunk boundary costs the actor a fixed hand-off (synchronise, ship the
+        chunk's tokens, launch the scorer's pass) - the cost that grows as chunks
+        shrink (Sec. 3.1, "Dynamic Control on Intra-step Overlap");
+      * the scorer's projections and MLPs cost a fixed number of FLOPs per token.
+    """
+    layers: int = 32
+    weight_bytes: float = 2 * 8.03e9                  # bf16 parameters
+    kv_bytes_per_token: float = 2 * 32 * 8 * 128 * 2  # K and V, 32 layers x 8 kv-heads x 128, bf16
+    decode_bytes_per_s: float = 5.0e12
+    decode_step_overhead_s: float = 30e-6
+    handoff_s: float = 2e-3
+    dense_flops_per_token: float = 2 * 8.03e9
+    dense_flops_per_s: float = 1.2e15
+
+    def decode_step_s(self, live_tokens: float) -> float:
+        return self.decode_step_overhead_s + (self.weight_bytes + live_tokens * self.kv_bytes_per_token) / self.decode_bytes_per_s
+
+    def dense_s(self, tokens: float) -> float:
+        return tokens * self.dense_flops_per_token / self.dense_flops_per_s
+
+
+def generation_times(prompt_len, resp_len, C: int, model: TimingModel) -> List[float]:
+    """Seconds the modelled actor needs for each chunk of C decode steps (the last chunk
+    may be shorter), with every unfinished sequence of the batch decoding in lockstep."""
+    P = np.asarray(prompt_len, dtype=np.int64)
+    R = np.asarray(resp_len, dtype=np.int64)
+    out: List[float] = []
+    longest = int(R.max()) if len(R) else 0
+    for c0 in range(0, longest, C):
+        t = model.handoff_s
+        for j in range(c0, min(c0 + C, longest)):
+            live = R > j
+            t += model.decode_step_s(float((P[live] + j).sum()))
+        out.append(t)
+    return out
+
+
+def pass_generation_time(kv_before, q_len, model: TimingModel) -> float:
+    """Seconds the modelled actor needs to produce one pass's rows: sequence i decodes
+    q_len[i] tokens on top of kv_before[i], all in lockstep, each step reading the
+    weights and the K/V of the sequences still decoding; plus one hand-off."""
+    kvb = np.asarray(kv_before, dtype=np.int64)
+    ql = np.asarray(q_len, dtype=np.int64)
+    t = model.handoff_s
+    for j in range(int(ql.max()) if len(ql) else 0):
+        live = ql > j
+        t += model.decode_step_s(float((kvb[live] + j).sum()))
+    return t
 
 
 def cpu_baseline(cfg, ep, budget_s: float = 12.0):
@@ -145,11 +205,11 @@ def overlap_study(args, cfg, torch, ob) -> int:
     hidden behind generation, and the step time that results, per chunk size.  The scorer's
     attention passes are measured here (library events around each pass's kernels, times the
     model's layer count); the generating side and the dense part of the scorer's layers come from
-    the stated synthetic model (workload.TimingModel).  The two sides are taken to run on separate
+    the stated synthetic model (TimingModel above).  The two sides are taken to run on separate
     accelerators.  The prompts are chunk 0 of the timeline, complete at time 0 (they are known before
     generation starts).  Baseline: generation, then one prefill of everything."""
     from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
-    from paper_2509_25762_amd.workload import TimingModel, build_episode, generation_times
+    from paper_2509_25762_amd.workload import build_episode
     model = TimingModel()
     ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
     candidates = [16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
@@ -218,11 +278,11 @@ def inter_step_study(args, cfg, torch, ob) -> int:
     B-th finisher instead of the slowest sequence and the unfinished ones carry their cached prefix
     over.  Every pass of the library's scheduler / slot pool / fused attention call is measured
     (library events, x the model's layer count); generation and the scorer's dense work come from the
-    stated synthetic model (workload.TimingModel); each iteration is one intra-step timeline
+    stated synthetic model (TimingModel above); each iteration is one intra-step timeline
     (oppo_overlap_timeline), iterations follow one another (the PPO update in between is the same
     for every Delta and left out).  Baseline: Delta = 0 without streaming (generate, then score once)."""
     from paper_2509_25762_amd.episode import BufferedRun
-    from paper_2509_25762_amd.workload import TimingModel, build_episode, pass_generation_time
+    from paper_2509_25762_amd.workload import build_episode
     model = TimingModel()
     B = cfg.batch
     n_seq = 4 * B

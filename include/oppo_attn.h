@@ -159,10 +159,12 @@ int oppo_qkv_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const
  * an empty cache.
  * workspace: device scratch for splitting long key ranges across workgroups
  * (partial results merged by a second kernel).  NULL / 0 bytes disables
- * splitting; otherwise it must hold at least
- * oppo_workspace_bytes(desc, batch, cu_q[batch]) bytes, 256-byte aligned.
+ * splitting; otherwise it must be 256-byte aligned and hold at least one partial
+ * slot (256 x (D + 2) x Hkv floats).  oppo_workspace_bytes(desc, batch,
+ * cu_q[batch]) is the size beyond which more does not help; a smaller one only
+ * limits how many pieces key ranges are cut into, never what is computed.
  * Errors: INVALID (nulls, bad cu_q, q_len_i > kv_len[i], kv_len[i] beyond the
- * slab), UNSUPPORTED, WORKSPACE, HIP.
+ * slab), UNSUPPORTED, WORKSPACE (misaligned, or smaller than one slot), HIP.
  */
 int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cache,
                             const int32_t* cu_q /* host [batch+1] */,
@@ -345,15 +347,19 @@ int oppo_overlap_timeline(int32_t n_chunks, const double* gen_s, const double* s
                           double* start_s, double* end_s, double* summary /* [3] */);
 
 /*
- * Bytes of workspace that let the attention entry points split key ranges for
- * any call with at most max_batch sequences and max_q_tokens query rows in
- * total.  Returns 0 for an unsupported desc or negative sizes.
+ * Bytes of workspace beyond which the attention entry points have no use for
+ * more, for any call with at most max_batch sequences and max_q_tokens query
+ * rows in total: one partial slot per piece that the planner may cut (bounded
+ * by the chip: a few per compute unit; and by the work: at most 32 pieces per
+ * query tile of 256 / (Hq / Hkv) tokens).  Returns 0 for an unsupported desc,
+ * negative sizes, or when there is nothing to split.
  */
 size_t oppo_workspace_bytes(const oppo_attn_desc* desc, int32_t max_batch, int32_t max_q_tokens);
 
 /*
- * Tuning knobs, process-wide, read at call time (not thread-safe against
- * concurrent calls).  They change how work is cut and ordered, never what is
+ * Tuning knobs, process-wide.  Every entry point takes one snapshot of them when
+ * it starts (under a lock), so setting them from another thread never changes a
+ * call half-way.  They change how work is cut and ordered, never what is
  * computed; tests use them to show that results do not depend on the cut.
  *   OPPO_OPT_SPLIT_KV : 0 = automatic (default: key ranges are cut where that
  *                       evens out the load of the persistent workgroups),
@@ -396,10 +402,17 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
  * the recorded events, writes the summed kernel time in milliseconds and the
  * number of launches since the last read into kernel_ms[3] / launches[3]
  * (host arrays; index 0 = attention kernel, 1 = split-KV merge kernel,
- * 2 = append kernel) and forgets them.  Not thread-safe.
+ * 2 = append kernel) and forgets them.  The list of events is shared by all
+ * threads (guarded by a lock): a read collects every thread's launches.
+ * oppo_profile_host reports what the attention entry points cost on the host
+ * while profiling was enabled, summed since the last read: host_us[0] =
+ * microseconds spent planning (cutting the pass into pieces and queues),
+ * host_us[1] = microseconds spent launching (argument marshalling and the
+ * runtime's launch calls), *calls = number of entry-point calls counted.
  */
 int oppo_profile_enable(int on);
 int oppo_profile_read(double* kernel_ms /* [3] */, int32_t* launches /* [3] */);
+int oppo_profile_host(double* host_us /* [2] */, int64_t* calls);
 
 /* Reason of the last failing call on this thread ("" if none). */
 const char* oppo_last_error(void);

@@ -31,7 +31,7 @@ OPT_NUM_CUS = 2
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append",
-    "oppo_profile_enable", "oppo_profile_read",
+    "oppo_profile_enable", "oppo_profile_read", "oppo_profile_host",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
@@ -92,6 +92,8 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_step.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp, vp,
                                     vp, ctypes.c_size_t, vp]
     lib.oppo_chunk_step.restype = ctypes.c_int
+    lib.oppo_profile_host.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.oppo_profile_host.restype = ctypes.c_int
     lib.oppo_full_prefill_ref.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, vp, vp, vp, vp, vp,
                                           ctypes.c_size_t, vp]
     lib.oppo_full_prefill_ref.restype = ctypes.c_int
@@ -171,6 +173,27 @@ def _dev_ptr(t) -> Optional[int]:
     if not t.is_contiguous():
         raise ValueError("device tensors must be contiguous")
     return t.data_ptr()
+
+
+def _need(t, nbytes: int, name: str) -> None:
+    """A device buffer handed to the library must hold at least `nbytes` and live on the GPU.
+    The C ABI carries no sizes for device buffers, and an undersized one would be read or
+    written out of bounds by a kernel, so it is refused here, where sizes are known.  Raw
+    integer addresses cannot be checked and are taken as they are."""
+    if t is None or isinstance(t, int) or nbytes <= 0:
+        return
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise ValueError(f"{name} holds {have} bytes, the call needs {nbytes}")
+    if getattr(t, "is_cuda", True) is False:
+        raise ValueError(f"{name} must be a device tensor")
+
+
+def _need_cache(desc, cache, name: str = "cache") -> None:
+    slots = int(cache.slot_begin[-1]) if len(cache.slot_begin) else 0
+    nbytes = slots * desc.num_kv_heads * desc.head_dim * 2
+    _need(getattr(cache, "k", None), nbytes, f"{name}.k")
+    _need(getattr(cache, "v", None), nbytes, f"{name}.v")
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -381,6 +404,9 @@ def oppo_rope(desc: AttnDesc, kv_before, cu_q, q, k_new, theta_base: float = 100
     """Rotates the pass's query rows and new key rows in place (either may be None)."""
     cu = _i32(cu_q)
     kvb = _i32(kv_before, cu.shape[0] - 1)
+    rows = int(cu[-1]) if cu.shape[0] else 0
+    _need(q, rows * desc.num_q_heads * desc.head_dim * 2, "q")
+    _need(k_new, rows * desc.num_kv_heads * desc.head_dim * 2, "k_new")
     _check(load().oppo_rope(ctypes.byref(desc), kvb.shape[0], _i32p(kvb), _i32p(cu), _dev_ptr(q), _dev_ptr(k_new),
                             float(theta_base), _stream_ptr(stream)))
 
@@ -422,6 +448,14 @@ def oppo_profile_read():
     return {k: ms[i] for i, k in enumerate(names)}, {k: n[i] for i, k in enumerate(names)}
 
 
+def oppo_profile_host():
+    """({'plan','launch'} -> host microseconds inside the attention entry points, number of calls) since the last read."""
+    us = (ctypes.c_double * 2)()
+    n = ctypes.c_int64(0)
+    _check(load().oppo_profile_host(us, ctypes.byref(n)))
+    return {"plan": us[0], "launch": us[1]}, n.value
+
+
 def oppo_chunk_schedule(prompt_len, resp_len, C: int, t: int):
     """Returns (kv_before, q_len, cu_q) as int32 numpy arrays."""
     P = _i32(prompt_len)
@@ -438,8 +472,19 @@ def oppo_workspace_bytes(desc: AttnDesc, max_batch: int, max_q_tokens: int) -> i
     return int(load().oppo_workspace_bytes(ctypes.byref(desc), max_batch, max_q_tokens))
 
 
+def _need_rows(desc: AttnDesc, cu: np.ndarray, **bufs) -> None:
+    """q / out hold cu[-1] rows of Hq heads, k_new / v_new of Hkv heads, qkv of Hq + 2 Hkv."""
+    rows = int(cu[-1]) if cu.shape[0] else 0
+    heads = {"q": desc.num_q_heads, "out": desc.num_q_heads, "q_out": desc.num_q_heads, "k_new": desc.num_kv_heads,
+             "v_new": desc.num_kv_heads, "qkv": desc.num_q_heads + 2 * desc.num_kv_heads}
+    for name, t in bufs.items():
+        _need(t, rows * heads[name] * desc.head_dim * 2, name)
+
+
 def oppo_kv_append(desc: AttnDesc, cache: KVCache, cu_q, k_new, v_new, stream=None) -> None:
     cu = _i32(cu_q, cache.batch + 1)
+    _need_rows(desc, cu, k_new=k_new, v_new=v_new)
+    _need_cache(desc, cache)
     _check(load().oppo_kv_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(k_new),
                                  _dev_ptr(v_new), _stream_ptr(stream)))
 
@@ -447,6 +492,8 @@ def oppo_kv_append(desc: AttnDesc, cache: KVCache, cu_q, k_new, v_new, stream=No
 def oppo_qkv_rope_append(desc: AttnDesc, cache: KVCache, cu_q, qkv, q_out, theta_base: float = 10000.0, stream=None) -> None:
     """Epilogue of a fused QKV projection: rotated queries to q_out, rotated keys and values into the cache."""
     cu = _i32(cu_q, cache.batch + 1)
+    _need_rows(desc, cu, qkv=qkv, q_out=q_out)
+    _need_cache(desc, cache)
     _check(load().oppo_qkv_rope_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(qkv),
                                        _dev_ptr(q_out), float(theta_base), _stream_ptr(stream)))
 
@@ -454,6 +501,9 @@ def oppo_qkv_rope_append(desc: AttnDesc, cache: KVCache, cu_q, qkv, q_out, theta
 def oppo_chunk_prefill_attn(desc: AttnDesc, cache: KVCache, cu_q, q, out, workspace=None, stream=None) -> None:
     cu = _i32(cu_q, cache.batch + 1)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _need_rows(desc, cu, q=q, out=out)
+    _need_cache(desc, cache)
+    _need(workspace, 1, "workspace")
     _check(load().oppo_chunk_prefill_attn(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
                                           _dev_ptr(out), _dev_ptr(workspace), ws_bytes, _stream_ptr(stream)))
 
@@ -461,6 +511,9 @@ def oppo_chunk_prefill_attn(desc: AttnDesc, cache: KVCache, cu_q, q, out, worksp
 def oppo_chunk_step(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, workspace=None, stream=None) -> None:
     cu = _i32(cu_q, cache.batch + 1)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _need_rows(desc, cu, q=q, k_new=k_new, v_new=v_new, out=out)
+    _need_cache(desc, cache)
+    _need(workspace, 1, "workspace")
     _check(load().oppo_chunk_step(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
                                   _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out), _dev_ptr(workspace), ws_bytes,
                                   _stream_ptr(stream)))
@@ -470,6 +523,8 @@ def oppo_full_prefill_ref(desc: AttnDesc, cu_seq, q, k, v, out, workspace=None, 
     cu = _i32(cu_seq)
     B = cu.shape[0] - 1
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _need_rows(desc, cu, q=q, out=out, k_new=k, v_new=v)
+    _need(workspace, 1, "workspace")
     _check(load().oppo_full_prefill_ref(ctypes.byref(desc), B, _i32p(cu), _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
                                         _dev_ptr(out), _dev_ptr(workspace), ws_bytes, _stream_ptr(stream)))
 

@@ -16,6 +16,7 @@
 //     absolute position pos0+t sees keys <= pos0+t.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -98,7 +99,10 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 // Written as inline assembly on purpose: for the intrinsic form the compiler
 // cannot tell the ring stages apart and waits for the copy before every later
 // LDS read, which would serialise the prefetch; the waits are placed by hand.
-// M0 is a reserved register that the compiler sets before each of its own uses.
+// M0 is written here.  It is a reserved register: the compiler sets it before each of its
+// own uses (LDS-DMA and GWS instructions, of which this kernel has none besides these), and
+// it refuses M0 on a clobber list ("reserved register ... may lead to undefined behaviour"),
+// so none is given.  The LDS addresses this produces are pinned by every GPU parity test.
 __device__ __forceinline__ void async_copy16(const void* gbase, uint32_t voff_bytes, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds_addr), "v"(voff_bytes), "s"(gbase) : "memory");
@@ -905,50 +909,71 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams P) {
 // ---------------------------------------------------------------------------------
 
 // Optional per-kernel timing: HIP events recorded on the launch stream right
-// before and after each kernel launch while enabled.
-struct EventPair { hipEvent_t a, b; int kind; };
+// before and after each kernel launch while enabled.  The list of pairs is shared by
+// all host threads and guarded by a lock.
+struct EventPair { hipEvent_t a, b; int kind; bool closed; };
+static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static std::vector<EventPair> g_prof_events;
 
-static void prof_begin(int kind, hipStream_t st) {
-  if (!g_prof_on) return;
+// Returns the index of the pair that was opened, or -1 (profiling off, or no event to be had:
+// then the launch is simply not timed).
+static int prof_begin(int kind, hipStream_t st) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  if (!g_prof_on) return -1;
   EventPair p;
   p.kind = kind;
-  if (hipEventCreate(&p.a) != hipSuccess) return;
+  p.closed = false;
+  if (hipEventCreate(&p.a) != hipSuccess) return -1;
   if (hipEventCreate(&p.b) != hipSuccess) {
     (void)hipEventDestroy(p.a);
-    return;
+    return -1;
   }
   (void)hipEventRecord(p.a, st);
   g_prof_events.push_back(p);
+  return (int)g_prof_events.size() - 1;
 }
-static void prof_end(hipStream_t st) {
-  if (!g_prof_on || g_prof_events.empty()) return;
-  (void)hipEventRecord(g_prof_events.back().b, st);
+static void prof_end(int pair, hipStream_t st) {
+  if (pair < 0) return;
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  if ((size_t)pair >= g_prof_events.size()) return;   // read (and cleared) by another thread meanwhile
+  (void)hipEventRecord(g_prof_events[(size_t)pair].b, st);
+  g_prof_events[(size_t)pair].closed = true;
 }
 int profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   g_prof_on = on != 0;
   return 0;
 }
+bool profile_is_on() {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  return g_prof_on;
+}
 int profile_read(double ms[3], int32_t launches[3]) {
   for (int k = 0; k < 3; ++k) ms[k] = 0.0, launches[k] = 0;
+  std::vector<EventPair> pairs;
+  {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    pairs.swap(g_prof_events);
+  }
   int rc = 0;
-  for (EventPair& p : g_prof_events) {
-    float t = 0.f;
-    hipError_t e = hipEventSynchronize(p.b);
-    if (e == hipSuccess) e = hipEventElapsedTime(&t, p.a, p.b);
-    if (e != hipSuccess) rc = (int)e;
-    else if (p.kind >= 0 && p.kind < 3) ms[p.kind] += t, launches[p.kind] += 1;
+  for (EventPair& p : pairs) {
+    if (p.closed) {
+      float t = 0.f;
+      hipError_t e = hipEventSynchronize(p.b);
+      if (e == hipSuccess) e = hipEventElapsedTime(&t, p.a, p.b);
+      if (e != hipSuccess) rc = (int)e;
+      else if (p.kind >= 0 && p.kind < 3) ms[p.kind] += t, launches[p.kind] += 1;
+    }
     (void)hipEventDestroy(p.a);
     (void)hipEventDestroy(p.b);
   }
-  g_prof_events.clear();
   return rc;
 }
 
 int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, const void* k_new, const void* v_new,
                      void* out, float* part_o, float* part_ml, const AttnItem* items, int n_items,
-                     const uint16_t* first, int n_queues, void* stream) {
+                     const uint16_t* first, int n_queues, void* stream, bool timed) {
   hipStream_t st = (hipStream_t)stream;
   if (n_items <= 0 || n_queues <= 0) return 0;
   if (n_items > kMaxAttnItems || n_queues > kMaxQueues) return (int)hipErrorInvalidValue;
@@ -972,7 +997,7 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   for (int i = 0; i < n_items; ++i) P.items[i] = items[i];
   dim3 grid((unsigned)(n_queues * ls.Hkv));
   const bool append = k_new != nullptr;
-  prof_begin(0, st);
+  const int pair = timed ? prof_begin(0, st) : -1;
   if (ls.D == 128) {
     if (append) hipLaunchKernelGGL((attn_fwd_kernel<128, true>), grid, dim3(512), 0, st, P);
     else hipLaunchKernelGGL((attn_fwd_kernel<128, false>), grid, dim3(512), 0, st, P);
@@ -980,12 +1005,12 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
     if (append) hipLaunchKernelGGL((attn_fwd_kernel<64, true>), grid, dim3(512), 0, st, P);
     else hipLaunchKernelGGL((attn_fwd_kernel<64, false>), grid, dim3(512), 0, st, P);
   }
-  prof_end(st);
+  prof_end(pair, st);
   return (int)hipGetLastError();
 }
 
 int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,
-                   const CombineItem* items, int n_items, void* stream) {
+                   const CombineItem* items, int n_items, void* stream, bool timed) {
   hipStream_t st = (hipStream_t)stream;
   for (int base = 0; base < n_items; base += kMaxCombineItems) {
     CombineParams P;
@@ -1004,7 +1029,7 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
     dim3 grid((unsigned)(n * ls.Hkv), (unsigned)(kTileRows / rpb)), block(256);
     int max_split = 0;
     for (int i = 0; i < n; ++i) max_split = items[base + i].nsplit > max_split ? items[base + i].nsplit : max_split;
-    prof_begin(1, st);
+    const int pair = timed ? prof_begin(1, st) : -1;
     if (ls.D == 128) {
       if (max_split <= 4) hipLaunchKernelGGL((combine_kernel<128, 4>), grid, block, 0, st, P);
       else if (max_split <= 8) hipLaunchKernelGGL((combine_kernel<128, 8>), grid, block, 0, st, P);
@@ -1014,7 +1039,7 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
       else if (max_split <= 8) hipLaunchKernelGGL((combine_kernel<64, 8>), grid, block, 0, st, P);
       else hipLaunchKernelGGL((combine_kernel<64, kMaxSplit>), grid, block, 0, st, P);
     }
-    prof_end(st);
+    prof_end(pair, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
@@ -1040,9 +1065,9 @@ int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void
     }
     (void)max_tok;
     dim3 grid((unsigned)n, (unsigned)((mt + kAppendTok - 1) / kAppendTok), 2), block(256);
-    prof_begin(2, st);
+    const int pair = prof_begin(2, st);
     hipLaunchKernelGGL(kv_append_kernel, grid, block, 0, st, P);
-    prof_end(st);
+    prof_end(pair, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }

@@ -86,11 +86,12 @@ struct LayerShape {
 // k_new / v_new null: keys and values come from k / v alone.  Otherwise the
 // kernel also appends: a sequence's keys from position pos0 - tile * TM on are
 // read from k_new / v_new (rows indexed like q) and copied into k / v.
+// timed: bracket the launch with an event pair while profiling is enabled.
 int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, const void* k_new, const void* v_new,
                      void* out, float* part_o, float* part_ml, const AttnItem* items, int n_items,
-                     const uint16_t* first, int n_queues, void* stream);
+                     const uint16_t* first, int n_queues, void* stream, bool timed);
 int launch_combine(const LayerShape& ls, void* out, const float* part_o, const float* part_ml,
-                   const CombineItem* items, int n_items, void* stream);
+                   const CombineItem* items, int n_items, void* stream, bool timed);
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
                   const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
 // q / k null: that array is left alone.  (rope.hip)
@@ -104,6 +105,7 @@ const char* hip_error_string(int err);
 // returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int profile_enable(int on);
+bool profile_is_on();
 int profile_read(double ms[3], int32_t launches[3]);  // 0 attention, 1 merge, 2 append
 
 // Bytes of one partial slot (all kv-heads): kTileRows rows x (D + 2) floats each.

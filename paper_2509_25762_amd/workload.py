@@ -187,62 +187,3 @@ def episode_work(cfg: Config, steps) -> List[Dict[str, float]]:
     """Per-step work of an episode; `steps` yields (kv_before[B], q_len[B])
     as produced by the chunk scheduler of whichever side is being measured."""
     return [step_work(cfg, np.asarray(kvb), np.asarray(ql)) for kvb, ql in steps]
-
-
-@dataclasses.dataclass(frozen=True)
-class TimingModel:
-    """Synthetic timing of what surrounds the measured attention passes: the generating
-    side (actor) and the dense part of the scorer's layers.  Stated figures, not
-    measurements - they stand in for the 8B-class models of the paper's runs (Sec. 4.1)
-    on one accelerator each, and only give the measured attention time something to be
-    hidden behind (Sec. 3.1):
-      * a decode step of the actor is bound by memory traffic: all weights plus the
-        K/V of every live token are read once per generated token;
-      * every chunk boundary costs the actor a fixed hand-off (synchronise, ship the
-        chunk's tokens, launch the scorer's pass) - the cost that grows as chunks
-        shrink (Sec. 3.1, "Dynamic Control on Intra-step Overlap");
-      * the scorer's projections and MLPs cost a fixed number of FLOPs per token.
-    """
-    layers: int = 32
-    weight_bytes: float = 2 * 8.03e9                  # bf16 parameters
-    kv_bytes_per_token: float = 2 * 32 * 8 * 128 * 2  # K and V, 32 layers x 8 kv-heads x 128, bf16
-    decode_bytes_per_s: float = 5.0e12
-    decode_step_overhead_s: float = 30e-6
-    handoff_s: float = 2e-3
-    dense_flops_per_token: float = 2 * 8.03e9
-    dense_flops_per_s: float = 1.2e15
-
-    def decode_step_s(self, live_tokens: float) -> float:
-        return self.decode_step_overhead_s + (self.weight_bytes + live_tokens * self.kv_bytes_per_token) / self.decode_bytes_per_s
-
-    def dense_s(self, tokens: float) -> float:
-        return tokens * self.dense_flops_per_token / self.dense_flops_per_s
-
-
-def generation_times(prompt_len, resp_len, C: int, model: TimingModel) -> List[float]:
-    """Seconds the modelled actor needs for each chunk of C decode steps (the last chunk
-    may be shorter), with every unfinished sequence of the batch decoding in lockstep."""
-    P = np.asarray(prompt_len, dtype=np.int64)
-    R = np.asarray(resp_len, dtype=np.int64)
-    out: List[float] = []
-    longest = int(R.max()) if len(R) else 0
-    for c0 in range(0, longest, C):
-        t = model.handoff_s
-        for j in range(c0, min(c0 + C, longest)):
-            live = R > j
-            t += model.decode_step_s(float((P[live] + j).sum()))
-        out.append(t)
-    return out
-
-
-def pass_generation_time(kv_before, q_len, model: TimingModel) -> float:
-    """Seconds the modelled actor needs to produce one pass's rows: sequence i decodes
-    q_len[i] tokens on top of kv_before[i], all in lockstep, each step reading the
-    weights and the K/V of the sequences still decoding; plus one hand-off."""
-    kvb = np.asarray(kv_before, dtype=np.int64)
-    ql = np.asarray(q_len, dtype=np.int64)
-    t = model.handoff_s
-    for j in range(int(ql.max()) if len(ql) else 0):
-        live = ql > j
-        t += model.decode_step_s(float((kvb[live] + j).sum()))
-    return t

@@ -343,3 +343,106 @@ def test_qkv_epilogue_validation_leaves_lengths_untouched(lib):
     # nobody has rows: legal, no device needed
     ob.oppo_qkv_rope_append(desc, cache, [0, 0, 0], None, None, stream=0)
     assert cache.kv_len.tolist() == [6, 0]
+
+
+def test_binding_refuses_undersized_or_host_buffers(lib):
+    """The C ABI carries no sizes for device buffers; the binding knows them and refuses, before the
+    library is called, a buffer smaller than the rows the call addresses or one that is not on the GPU."""
+    import torch
+    desc = _desc()
+    rows, Hq, Hkv, D = 6, 32, 8, 128
+    cu = [0, 2, 6]
+
+    class Dev:
+        """Stands in for a device tensor of n bytes (nothing dereferences it: every call below
+        fails in the binding, or has nothing to do)."""
+        def __init__(self, n, is_cuda=True):
+            self.n, self.is_cuda = n, is_cuda
+
+        def is_contiguous(self):
+            return True
+
+        def data_ptr(self):
+            return 0x100000
+
+        def numel(self):
+            return self.n
+
+        def element_size(self):
+            return 1
+
+    slabs = 30 * Hkv * D * 2
+    cache = ob.KVCache(Dev(slabs), Dev(slabs), np.array([0, 10, 30]), np.array([2, 3]))
+    q_ok, kv_ok = Dev(rows * Hq * D * 2), Dev(rows * Hkv * D * 2)
+    q_small, kv_small = Dev(rows * Hq * D * 2 - 2), Dev(rows * Hkv * D * 2 - 2)
+    with pytest.raises(ValueError, match="q holds"):
+        ob.oppo_chunk_step(desc, cache, cu, q_small, kv_ok, kv_ok, q_ok, stream=0)
+    with pytest.raises(ValueError, match="v_new holds"):
+        ob.oppo_chunk_step(desc, cache, cu, q_ok, kv_ok, kv_small, q_ok, stream=0)
+    with pytest.raises(ValueError, match="k_new holds"):
+        ob.oppo_kv_append(desc, cache, cu, kv_small, kv_ok, stream=0)
+    with pytest.raises(ValueError, match="out holds"):
+        ob.oppo_chunk_prefill_attn(desc, cache, cu, q_ok, q_small, stream=0)
+    with pytest.raises(ValueError, match="qkv holds"):
+        ob.oppo_qkv_rope_append(desc, cache, cu, Dev(rows * (Hq + 2 * Hkv) * D * 2 - 2), q_ok, stream=0)
+    with pytest.raises(ValueError, match="k_new holds"):
+        ob.oppo_rope(desc, [2, 3], cu, q_ok, kv_small, stream=0)
+    with pytest.raises(ValueError, match="q holds"):
+        ob.oppo_full_prefill_ref(desc, cu, q_small, kv_ok, kv_ok, q_ok, stream=0)
+    short = ob.KVCache(Dev(slabs - 2), Dev(slabs), np.array([0, 10, 30]), np.array([2, 3]))
+    with pytest.raises(ValueError, match=r"cache\.k holds"):
+        ob.oppo_chunk_step(desc, short, cu, q_ok, kv_ok, kv_ok, q_ok, stream=0)
+    with pytest.raises(ValueError, match="must be a device tensor"):
+        ob.oppo_chunk_step(desc, cache, cu, Dev(rows * Hq * D * 2, is_cuda=False), kv_ok, kv_ok, q_ok, stream=0)
+    host = torch.zeros((rows, Hq, D), dtype=torch.int16)                   # a real tensor in host memory
+    with pytest.raises(ValueError, match="must be a device tensor"):
+        ob.oppo_chunk_step(desc, cache, cu, host, kv_ok, kv_ok, q_ok, stream=0)
+    with pytest.raises(ValueError, match="workspace must be a device tensor"):
+        ob.oppo_chunk_prefill_attn(desc, cache, cu, q_ok, q_ok, torch.zeros(1 << 21, dtype=torch.uint8), stream=0)
+    assert cache.kv_len.tolist() == [2, 3]
+
+
+def test_workspace_size_follows_the_work(lib):
+    """oppo_workspace_bytes honours its arguments, and a workspace smaller than it (but at least one
+    slot) is accepted: it only bounds the number of partial pieces."""
+    desc = _desc()
+    slot = 8 * 256 * 130 * 4
+    assert ob.oppo_workspace_bytes(desc, 1, 64) == 2 * 32 * slot          # one full tile + one ragged tile, 32 pieces each
+    assert ob.oppo_workspace_bytes(desc, 64, 1 << 16) == (6 * 256 // 8 + 1) * slot   # bounded by the chip
+    assert ob.oppo_workspace_bytes(desc, 0, 0) == 0
+    full = ob.oppo_plan_debug(desc, [3000], [256], ob.oppo_workspace_bytes(desc, 1, 256))
+    assert np.sum(full[:, 6] >= 0) > 20                                   # one straggler: cut for all 32 queues
+    few = ob.oppo_plan_debug(desc, [3000], [256], 20 * slot)              # the same with twenty slots
+    parts = few[few[:, 6] >= 0][:, 6]
+    assert len(parts) <= 20 and (len(parts) == 0 or parts.max() < 20)
+    _check_plan(desc, [3000], [256], few, 64)
+    none = ob.oppo_plan_debug(desc, [3000], [256], slot)                  # one slot: nothing can be split
+    assert np.all(none[:, 6] == -1) and len(none) == 4
+
+
+def test_options_are_snapshotted_per_call_and_settable_from_threads(lib):
+    """oppo_set_option from another thread while plans are being made: every plan is a valid plan of
+    one of the two policies (no call sees a half-changed set), and nothing crashes."""
+    import threading
+    desc = _desc()
+    ws = ob.oppo_workspace_bytes(desc, 64, 1 << 16)
+    kvb, ql = np.array([3000, 1200, 40]), np.array([256, 256, 100])
+    stop = threading.Event()
+
+    def flip():
+        i = 0
+        while not stop.is_set():
+            ob.oppo_set_option(ob.OPT_SPLIT_KV, 1 if i & 1 else 4)
+            i += 1
+
+    th = threading.Thread(target=flip)
+    th.start()
+    try:
+        for _ in range(300):
+            items = ob.oppo_plan_debug(desc, kvb, ql, ws)
+            n_parts = _check_plan(desc, kvb, ql, items, 64)
+            assert n_parts == 0 or n_parts >= 8
+    finally:
+        stop.set()
+        th.join()
+        ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)

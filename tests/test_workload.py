@@ -74,7 +74,7 @@ def test_timing_model_of_the_generating_side():
     """The synthetic timing model that stands in for the actor (stated figures, not the method):
     a decode step reads the weights and every live token's K/V once; a chunk is its steps plus one
     hand-off; per-chunk and per-pass bookkeeping agree."""
-    from paper_2509_25762_amd.workload import TimingModel, generation_times, pass_generation_time
+    from bench import TimingModel, generation_times, pass_generation_time
     m = TimingModel()
     assert m.decode_step_s(0) == pytest.approx(m.decode_step_overhead_s + m.weight_bytes / m.decode_bytes_per_s)
     assert m.decode_step_s(1000) - m.decode_step_s(0) == pytest.approx(1000 * m.kv_bytes_per_token / m.decode_bytes_per_s)
