@@ -192,6 +192,33 @@ int oppo_chunk_step(const oppo_attn_desc* desc, oppo_kv_cache* cache,
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * oppo_chunk_step for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, checks, results and length updates as
+ * oppo_chunk_step, but the partial results of split key ranges go to a scratch
+ * buffer built into the library (a device array of oppo_static_scratch_bytes()
+ * = 64 MiB in the library's code object; every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates no device memory,
+ * creates no events (oppo_profile_enable does not time it) and frees nothing;
+ * the buffer's address on the current device is looked up on the first call
+ * on that device.
+ * Limit: the buffer must hold the partial results of one fully split query tile,
+ * 32 x 256 x (D + 2) x Hkv floats, i.e. Hkv x (D + 2) <= 2048 (D = 128: up to 15
+ * kv-heads, D = 64: up to 31); wider layers get OPPO_ERR_UNSUPPORTED and the
+ * message says so.  Within the limit the buffer only bounds how finely key
+ * ranges are cut (63 slots for Hkv = 8, D = 128).
+ * All calls on one GPU share the one buffer and nothing in it needs clearing
+ * (every partial row is written before it is read), but two calls whose work
+ * overlaps in time on one GPU - different streams, or different host threads -
+ * race on it: callers serialise them, e.g. by using one stream.
+ */
+int oppo_chunk_step_noalloc(const oppo_attn_desc* desc, oppo_kv_cache* cache,
+                            const int32_t* cu_q /* host [batch+1] */,
+                            const void* q, const void* k_new, const void* v_new, void* out,
+                            void* stream);
+size_t oppo_static_scratch_bytes(void);
+
+/*
  * One-shot causal prefill of whole sequences, without a cache: the reference
  * side of the streaming-equivalence invariant (Sec. 3.1, Eq. 3) on the device.
  * Sequence i owns rows [cu_seq[i], cu_seq[i+1]) of q/out (device bf16

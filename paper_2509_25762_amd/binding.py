@@ -31,7 +31,7 @@ OPT_NUM_CUS = 2
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append",
-    "oppo_profile_enable", "oppo_profile_read", "oppo_profile_host",
+    "oppo_profile_enable", "oppo_profile_read", "oppo_profile_host", "oppo_chunk_step_noalloc", "oppo_static_scratch_bytes",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
@@ -92,6 +92,10 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_step.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp, vp,
                                     vp, ctypes.c_size_t, vp]
     lib.oppo_chunk_step.restype = ctypes.c_int
+    lib.oppo_chunk_step_noalloc.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp, vp, vp]
+    lib.oppo_chunk_step_noalloc.restype = ctypes.c_int
+    lib.oppo_static_scratch_bytes.argtypes = []
+    lib.oppo_static_scratch_bytes.restype = ctypes.c_size_t
     lib.oppo_profile_host.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.oppo_profile_host.restype = ctypes.c_int
     lib.oppo_full_prefill_ref.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, vp, vp, vp, vp, vp,
@@ -517,6 +521,19 @@ def oppo_chunk_step(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, 
     _check(load().oppo_chunk_step(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
                                   _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out), _dev_ptr(workspace), ws_bytes,
                                   _stream_ptr(stream)))
+
+
+def oppo_chunk_step_noalloc(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, stream=None) -> None:
+    """oppo_chunk_step with the library's built-in scratch buffer instead of a workspace."""
+    cu = _i32(cu_q, cache.batch + 1)
+    _need_rows(desc, cu, q=q, k_new=k_new, v_new=v_new, out=out)
+    _need_cache(desc, cache)
+    _check(load().oppo_chunk_step_noalloc(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
+                                          _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out), _stream_ptr(stream)))
+
+
+def oppo_static_scratch_bytes() -> int:
+    return int(load().oppo_static_scratch_bytes())
 
 
 def oppo_full_prefill_ref(desc: AttnDesc, cu_seq, q, k, v, out, workspace=None, stream=None) -> None:

@@ -852,6 +852,35 @@ int oppo_chunk_step(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int3
   return OPPO_OK;
 }
 
+size_t oppo_static_scratch_bytes(void) { return oppo::kStaticScratchBytes; }
+
+int oppo_chunk_step_noalloc(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q, const void* q,
+                            const void* k_new, const void* v_new, void* out, void* stream) {
+  oppo::LayerShape ls;
+  std::vector<SeqView> seqs;
+  int rc = chunk_step_checks(desc, cache, cu_q, &ls, &seqs);
+  if (rc) return rc;
+  // the built-in buffer has to hold the partial results of at least one fully split
+  // query tile of this layer shape
+  const size_t one = oppo::part_slot_bytes(ls.Hkv, ls.D);
+  if (one * (size_t)oppo::kMaxSplit > oppo::kStaticScratchBytes)
+    return fail(OPPO_ERR_UNSUPPORTED,
+                "layer too wide for the built-in scratch buffer: Hkv x (D + 2) = %d exceeds %zu; use oppo_chunk_step "
+                "with a workspace of the caller's",
+                ls.Hkv * (ls.D + 2), oppo::kStaticScratchBytes / ((size_t)oppo::kMaxSplit * oppo::kTileRows * sizeof(float)));
+  if (seqs.empty()) return OPPO_OK;
+  if (!cache->k || !cache->v || !q || !k_new || !v_new || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
+  void* scratch = nullptr;
+  const int e = oppo::static_scratch(&scratch);
+  if (e) return fail(OPPO_ERR_HIP, "address of the built-in scratch buffer: %s", oppo::hip_error_string(e));
+  // (no event pairs here: creating them would allocate)
+  rc = run_attention(options_now(), ls, seqs, q, cache->k, cache->v, k_new, v_new, out, scratch,
+                     oppo::kStaticScratchBytes, stream, false);
+  if (rc) return rc;
+  for (int32_t i = 0; i < cache->batch; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
+  return OPPO_OK;
+}
+
 int oppo_full_prefill_ref(const oppo_attn_desc* desc, int32_t B, const int32_t* cu_seq, const void* q, const void* k,
                           const void* v, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   oppo::LayerShape ls;

@@ -971,6 +971,32 @@ int profile_read(double ms[3], int32_t launches[3]) {
   return rc;
 }
 
+// Scratch buffer of the entry point that allocates nothing (partial results of split key
+// ranges).  The array's name is a host-side stand-in for the symbol: kernels are given the
+// address hipGetSymbolAddress reports for the current device, looked up once per device.
+// Nothing in it has to start at zero: every partial row is written before it is read.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return 0;
+}
+
 int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, const void* k_new, const void* v_new,
                      void* out, float* part_o, float* part_ml, const AttnItem* items, int n_items,
                      const uint16_t* first, int n_queues, void* stream, bool timed) {

@@ -52,6 +52,12 @@ int launch_qkv_rope_append(const LayerShape&, const void*, void*, void*, void*, 
 
 const char* hip_error_string(int) { return "launcher stub refused the work list"; }
 
+int static_scratch(void** ptr) {
+  static void* block = malloc(256);   // an address only: nothing dereferences it on the host
+  *ptr = block;
+  return 0;
+}
+
 int profile_enable(int on) {
   g_profile_on = on;
   return 0;

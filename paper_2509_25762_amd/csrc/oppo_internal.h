@@ -101,6 +101,12 @@ int launch_qkv_rope_append(const LayerShape& ls, const void* qkv, void* q_out, v
                            const QkvItem* items, int n_items, double theta_base, void* stream);
 const char* hip_error_string(int err);
 
+// The built-in scratch buffer of the entry point that allocates nothing: a device array
+// of this many bytes that lives in the library's code object, one copy per GPU.
+// static_scratch gives its address on the current device (looked up once per device).
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+int static_scratch(void** ptr);
+
 // Records the reason of a failing call (thread-local, read by oppo_last_error) and
 // returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));

@@ -150,6 +150,12 @@ static void abi_errors() {
   CHECK(oppo_chunk_step(&d, &cache, cu_ok, fake(1), nullptr, fake(3), fake(4), nullptr, 0, nullptr) == OPPO_ERR_INVALID);
   CHECK(oppo_chunk_step(&d, &cache, cu_ok, fake(1), fake(2), fake(3), fake(4), nullptr, 0, nullptr) == OPPO_OK);
   CHECK(kv_len[0] == 7 && kv_len[1] == 1);
+  CHECK(oppo_chunk_step_noalloc(&d, &cache, cu_over, fake(1), fake(2), fake(3), fake(4), nullptr) == OPPO_ERR_CAPACITY);
+  oppo_attn_desc wide{16 * 4, 16, 128, 0.1f};
+  CHECK(oppo_chunk_step_noalloc(&wide, &cache, cu_ok, fake(1), fake(2), fake(3), fake(4), nullptr) == OPPO_ERR_UNSUPPORTED);
+  CHECK(kv_len[0] == 7 && kv_len[1] == 1);
+  CHECK(oppo_chunk_step_noalloc(&d, &cache, cu_ok, fake(1), fake(2), fake(3), fake(4), nullptr) == OPPO_OK);
+  CHECK(kv_len[0] == 8 && kv_len[1] == 2);
   CHECK(oppo_chunk_prefill_attn(&d, &cache, cu_ok, fake(1), fake(2), fake(0x10001), 1 << 30, nullptr) == OPPO_ERR_WORKSPACE);
   CHECK(oppo_chunk_prefill_attn(&d, &cache, cu_ok, fake(1), fake(2), fake(0x10000), 4096, nullptr) == OPPO_ERR_WORKSPACE);
   int32_t cu_many[3] = {0, 1, 4};

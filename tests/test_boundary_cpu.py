@@ -379,6 +379,8 @@ def test_binding_refuses_undersized_or_host_buffers(lib):
         ob.oppo_chunk_step(desc, cache, cu, q_small, kv_ok, kv_ok, q_ok, stream=0)
     with pytest.raises(ValueError, match="v_new holds"):
         ob.oppo_chunk_step(desc, cache, cu, q_ok, kv_ok, kv_small, q_ok, stream=0)
+    with pytest.raises(ValueError, match="out holds"):
+        ob.oppo_chunk_step_noalloc(desc, cache, cu, q_ok, kv_ok, kv_ok, q_small, stream=0)
     with pytest.raises(ValueError, match="k_new holds"):
         ob.oppo_kv_append(desc, cache, cu, kv_small, kv_ok, stream=0)
     with pytest.raises(ValueError, match="out holds"):
@@ -400,6 +402,27 @@ def test_binding_refuses_undersized_or_host_buffers(lib):
     with pytest.raises(ValueError, match="workspace must be a device tensor"):
         ob.oppo_chunk_prefill_attn(desc, cache, cu, q_ok, q_ok, torch.zeros(1 << 21, dtype=torch.uint8), stream=0)
     assert cache.kv_len.tolist() == [2, 3]
+
+
+def test_noalloc_entry_point_validation(lib):
+    """oppo_chunk_step_noalloc: the checks of oppo_chunk_step, plus the limit its built-in scratch
+    buffer puts on the layer's width; all before any device is touched."""
+    assert ob.oppo_static_scratch_bytes() == 64 << 20
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 0])
+    for cu, code in [([0, 3, 6], ob.OPPO_ERR_CAPACITY), ([1, 3, 6], ob.OPPO_ERR_INVALID), ([0, 3, 2], ob.OPPO_ERR_INVALID)]:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_chunk_step_noalloc(desc, cache, cu, 0x3000, 0x4000, 0x5000, 0x6000, stream=0)
+        assert e.value.code == code and cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:                               # 16 kv-heads of 128: 16 x 130 > 2048
+        ob.oppo_chunk_step_noalloc(_desc(Hq=64, Hkv=16), cache, [0, 1, 2], 0x3000, 0x4000, 0x5000, 0x6000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_UNSUPPORTED and "scratch" in e.value.message
+    assert cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:
+        ob.oppo_chunk_step_noalloc(desc, cache, [0, 1, 2], 0x3000, None, 0x5000, 0x6000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID and cache.kv_len.tolist() == [6, 0]
+    ob.oppo_chunk_step_noalloc(desc, cache, [0, 0, 0], None, None, None, None, stream=0)   # nobody has rows
+    assert cache.kv_len.tolist() == [6, 0]
 
 
 def test_workspace_size_follows_the_work(lib):
