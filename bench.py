@@ -8,14 +8,23 @@ oppo_chunk_step (KV append fused into the chunked-prefill attention; with
 set of unfinished sequences.  Prompts are prefilled once before the timed
 region (reported separately).  Inputs are synthetic and resident in HBM.
 
-Prints ONE JSON line: `value` = algorithmic attention FLOPs of the episode per
-second of wall time over the timed episodes (TFLOP/s); `roofline` = the
-attention kernel alone (FLOPs, or bytes on a workload the memory roof binds,
-per second of kernel time measured with HIP events on the launch stream,
-against the chip's published peak; `traffic` = HBM bytes per launch measured
-with rocprofv3 counters); `cpu_baseline` = the float64 oracle timed on a bounded
-sample of the same workload.  Other modes (--deferral, --chunk-sweep, --overlap,
---inter-step, --contention) print one JSON line of their own.
+Prints ONE JSON line.  Headline = the Llama-3-8B-shape workload (config 2):
+`value` = algorithmic attention FLOPs of the episode per second of wall time over
+the timed episodes (TFLOP/s); `roofline` = the attention kernel alone (FLOPs, or
+bytes on a workload the memory roof binds, per second of kernel time measured
+with HIP events on the launch stream, against the chip's published peak;
+`traffic` = HBM bytes per launch measured with rocprofv3 counters, read from
+profiles/hbm_traffic.json); `step0` = the full-batch first pass on its own;
+`pass_cold` = the same episodes interleaved pass by pass over the cache copies,
+so that no pass finds the previous pass's keys in the last-level cache;
+`host_us_per_pass` = what a pass costs on the host; `per_config` = the other
+synthetic workloads measured the same way (and a parity bit for the tiny one);
+`cpu_baseline` = the float64 oracle timed on a bounded sample of the headline
+workload, single-threaded and over a process pool.  Before any timed region the
+GPU is kept busy until at least SETTLE_MS of load have run, whatever --warmup
+says: after idling, the core clock needs tens of milliseconds of load to settle.
+Other modes (--deferral, --chunk-sweep, --overlap, --inter-step, --contention,
+--traffic-from ...) print one JSON line of their own.
 """
 from __future__ import annotations
 
@@ -36,10 +45,38 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
-# HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
-# scaled by what the same counters read for the append kernel (a plain copy of known
-# size); see profiles/attn_fwd_kernel_config2.md and profiles/attn_fwd_kernel_config3_traffic.md.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {2: 259.5e6, 3: 523.6e6}
+SETTLE_MS = 200.0            # load the GPU has seen before a timed region starts, at least
+# HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by
+# what the same counters read for a plain copy of known size: written by `bench.py --traffic-from`
+# into this file together with a fingerprint of the kernel and planner sources it was measured on.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+TRAFFIC_SOURCES = ["paper_2509_25762_amd/csrc/kernels.hip", "paper_2509_25762_amd/csrc/api.cpp",
+                   "paper_2509_25762_amd/csrc/oppo_internal.h"]
+
+
+def source_fingerprint() -> str:
+    """Hash of the sources that decide how many bytes a launch moves (kernel, planner)."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(config_index: int):
+    """(bytes per launch or None, note): the tracked measurement if it was taken on these sources."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            data = json.load(f)
+    except (OSError, ValueError):
+        return None, "no tracked measurement (profiles/hbm_traffic.json missing)"
+    entry = data.get("configs", {}).get(str(config_index))
+    if entry is None:
+        return None, "not measured for this workload"
+    if data.get("source_fingerprint") != source_fingerprint():
+        return None, f"stale: measured at commit {data.get('commit', '?')} on other kernel/planner sources"
+    return float(entry["traffic_bytes_per_launch"]), f"measured at commit {data.get('commit', '?')}"
 
 
 @dataclasses.dataclass(frozen=True)
@@ -101,38 +138,85 @@ def pass_generation_time(kv_before, q_len, model: TimingModel) -> float:
     return t
 
 
-def cpu_baseline(cfg, ep, budget_s: float = 12.0):
-    """Times the float64 oracle, as it stands, on a bounded sample: whole
-    sequences of the workload (one-shot causal attention over prompt+response,
-    all heads; only the response rows' share of the FLOPs is credited), taken
-    in order of closeness to the median length until the time budget is spent."""
+def _oracle_unit(job):
+    """One (sequence, q-head) unit of the oracle: the response rows of that head over the head's keys."""
+    from oracle import bf16_bits_to_f64, causal_attention
+    qb, kb, vb, P, R, scale = job
+    causal_attention(bf16_bits_to_f64(qb), bf16_bits_to_f64(kb), bf16_bits_to_f64(vb), P + np.arange(R), scale)
+    return 4.0 * qb.shape[-1] * (R * P + R * (R + 1) / 2.0)
+
+
+def cpu_baseline(cfg, ep, budget_s: float = 8.0):
+    """Times the float64 oracle, as it stands, on a bounded sample of the workload, two ways:
+    single-threaded (BLAS limited to one thread) over whole sequences nearest the median length
+    (one-shot causal attention over prompt + response, all heads; only the response rows' share of
+    the FLOPs is credited), and with a process pool over (sequence, q-head) units on all cores the
+    process may use.  Must run before this process touches the GPU (the pool forks)."""
+    import multiprocessing as mp
     from oracle import bf16_bits_to_f64, causal_attention
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        threads = len(os.sched_getaffinity(0))
+        threadpool_limits = None
+        blas_threads = None
+    cores = len(os.sched_getaffinity(0))
     n = ep.prompt_len.astype(np.int64) + ep.resp_len
     order = np.argsort(np.abs(n - np.median(n)), kind="stable")
-    flops = 0.0
-    used = []
-    t0 = time.perf_counter()
-    for i in order:
+
+    def seq_arrays(i):
         lo = int(ep.tok_begin[i])
         P, R = int(ep.prompt_len[i]), int(ep.resp_len[i])
-        q = bf16_bits_to_f64(ep.q[lo + P:lo + P + R])
-        k = bf16_bits_to_f64(ep.k[lo:lo + P + R])
-        v = bf16_bits_to_f64(ep.v[lo:lo + P + R])
-        causal_attention(q, k, v, P + np.arange(R), cfg.softmax_scale)
-        flops += 4.0 * cfg.head_dim * cfg.num_q_heads * (R * P + R * (R + 1) / 2.0)
-        used.append(int(i))
-        if time.perf_counter() - t0 > budget_s:
-            break
-    dt = time.perf_counter() - t0
+        return ep.q[lo + P:lo + P + R], ep.k[lo:lo + P + R], ep.v[lo:lo + P + R], P, R
+
+    def single():
+        flops, used, t0 = 0.0, 0, time.perf_counter()
+        for i in order:
+            qb, kb, vb, P, R = seq_arrays(i)
+            causal_attention(bf16_bits_to_f64(qb), bf16_bits_to_f64(kb), bf16_bits_to_f64(vb), P + np.arange(R), cfg.softmax_scale)
+            flops += 4.0 * cfg.head_dim * cfg.num_q_heads * (R * P + R * (R + 1) / 2.0)
+            used += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        return flops, used, time.perf_counter() - t0
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            f1, n1, dt1 = single()
+    else:
+        f1, n1, dt1 = single()
+    # process pool: units of one (sequence, q-head), handed out until the budget is spent
+    G = cfg.num_q_heads // cfg.num_kv_heads
+    workers = max(1, cores)
+
+    def units():
+        for i in order:
+            qb, kb, vb, P, R = seq_arrays(i)
+            for h in range(cfg.num_q_heads):
+                g = h // G
+                yield (np.ascontiguousarray(qb[:, h:h + 1]), np.ascontiguousarray(kb[:, g:g + 1]),
+                       np.ascontiguousarray(vb[:, g:g + 1]), P, R, cfg.softmax_scale)
+
+    fp, np_units, t0 = 0.0, 0, time.perf_counter()
+    if threadpool_limits is not None:
+        limiter = threadpool_limits(limits=1)     # inherited by the forked workers: one BLAS thread each
+    with mp.get_context("fork").Pool(workers) as pool:
+        for got in pool.imap_unordered(_oracle_unit, units(), chunksize=1):
+            fp += got
+            np_units += 1
+            if time.perf_counter() - t0 > budget_s:
+                pool.terminate()
+                break
+    dtp = time.perf_counter() - t0
+    if threadpool_limits is not None:
+        limiter.restore_original_limits()
     return {
-        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{len(used)} of {cfg.batch} sequences nearest the median length, response rows x all heads, "
-                  f"float64 numpy, {dt:.1f} s",
+        "value": fp / dtp / 1e12, "unit": "TFLOP/s", "cores": int(workers), "kind": "oracle",
+        "sample": f"process pool of {workers} workers (one BLAS thread each) over {np_units} (sequence, q-head) units of the "
+                  f"sequences nearest the median length, response rows, float64 numpy, {dtp:.1f} s",
+        "single_thread": {"value": f1 / dt1 / 1e12, "unit": "TFLOP/s", "cores": 1,
+                          "sample": f"{n1} whole sequences nearest the median length, all heads, {dt1:.1f} s"},
+        "affinity_cores": int(cores), "blas_threads": blas_threads,
     }
 
 
@@ -785,6 +869,9 @@ def main() -> int:
                     help="colocation study: the streamed episode on one stream and a memory-bound decode-like load "
                          "(bf16 matrix-vector products) on another, alone and together, with the attention launch "
                          "restricted to 256 / 192 / 128 compute units (OPPO_OPT_NUM_CUS), without and with CU masks on the two streams")
+    ap.add_argument("--single", action="store_true", help="only the workload named by --config, no per_config block")
+    ap.add_argument("--traffic-from", type=str, default="", metavar="DIR",
+                    help="no GPU work: read rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE csv files from DIR and write profiles/hbm_traffic.json")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
@@ -797,13 +884,16 @@ def main() -> int:
     from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
     from paper_2509_25762_amd.workload import CONFIGS, build_episode, episode_work
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    ob.load()
-    if args.split:
-        ob.oppo_set_option(ob.OPT_SPLIT_KV, args.split)
     cfg = CONFIGS[args.config]
+    special = (args.deferral >= 0 or args.chunk_sweep or args.overlap or args.inter_step or args.rope or args.qkv_epilogue
+               or args.layer_path or args.thin_pass or args.steady or args.contention)
+    if special:
+        if not torch.cuda.is_available():
+            print("bench.py: no GPU visible", file=sys.stderr)
+            return 2
+        ob.load()
+        if args.split:
+            ob.oppo_set_option(ob.OPT_SPLIT_KV, args.split)
     if args.deferral >= 0:
         return deferral_bench(args, cfg, torch, ob)
     if args.chunk_sweep:
@@ -824,15 +914,99 @@ def main() -> int:
         return steady_bench(args, cfg, torch, ob)
     if args.contention:
         return contention_study(args, cfg, torch, ob)
-    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    if args.traffic_from:
+        return traffic_from(args)
+    threads = min(16, len(os.sched_getaffinity(0)))
+    ep = build_episode(cfg, threads=threads)
+    # the oracle first: its process pool forks, which has to happen before this process touches the GPU
+    baseline = None if args.no_cpu_baseline else cpu_baseline(cfg, ep)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ob.load()
+    if args.split:
+        ob.oppo_set_option(ob.OPT_SPLIT_KV, args.split)
+    head = measure_workload(cfg, ep, args, torch, ob, steps=args.steps, warmup=args.warmup, details=args.details)
+    del ep
+    line = {
+        "metric": "chunked-prefill attn TFLOP/s + KV GB/s, % of MI355X roofline, 1 GPU",
+        "value": head["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": head["config"],
+    }
+    for key in ("settle_ms", "kv_read_GBps", "total_GBps", "frac_of_roofline_episode", "frac_mfma_peak", "frac_hbm_peak",
+                "prompt_prefill_ms", "roofline", "append_kernel_ms_per_step", "merge_kernel_ms_per_step", "step0",
+                "pass_cold", "host_us_per_pass"):
+        line[key] = head[key]
+    per = {}
+    if not args.single:
+        for ci in sorted(CONFIGS):
+            if ci == cfg.index:
+                continue
+            c = CONFIGS[ci]
+            e = build_episode(c, threads=threads)
+            if ci == 1:
+                per["1"] = tiny_parity(c, e, torch, ob)
+            else:
+                r = measure_workload(c, e, args, torch, ob, steps=None, warmup=3, details="")
+                rf = r["roofline"]
+                per[str(ci)] = {"workload": r["config"]["workload"], "value": r["value"], "unit": "TFLOP/s",
+                                "ms_per_step": r["ms_per_step"], "steps": r["steps"], "kv_read_GBps": r["kv_read_GBps"],
+                                "total_GBps": r["total_GBps"], "bound": rf["bound"], "frac": rf["frac"],
+                                "achieved": rf["achieved"], "achieved_unit": rf["unit"], "traffic": rf["traffic"],
+                                "frac_of_roofline_episode": r["frac_of_roofline_episode"], "step0": r["step0"],
+                                "pass_cold_value": r["pass_cold"]["value"], "merge_kernel_ms_per_step": r["merge_kernel_ms_per_step"],
+                                "host_us_per_pass": r["host_us_per_pass"]}
+            del e
+            gc.collect()
+            torch.cuda.empty_cache()
+    line["per_config"] = per
+    line["cpu_baseline"] = baseline
+    print(json.dumps(line))
+    return 0
+
+
+def tiny_parity(cfg, ep, torch, ob):
+    """The tiny workload streamed through the library and compared, every row, with the float64
+    oracle's one-shot prefill (tolerance of the parity tests); the cache bit for bit."""
+    from oracle import bf16_bits_to_f64, full_prefill
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    se = StreamedEpisode(ep, uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk))
+    se.run()
+    torch.cuda.synchronize()
+    got = bf16_bits_to_f64(se.scatter_outputs().cpu().numpy().view(np.uint16))
+    worst, total, count, cache_ok = 0.0, 0.0, 0, True
+    ck = se.cache_k.cpu().numpy().view(np.uint16)
+    cv = se.cache_v.cpu().numpy().view(np.uint16)
+    for i in range(cfg.batch):
+        lo, hi = int(ep.tok_begin[i]), int(ep.tok_begin[i + 1])
+        ref = full_prefill(bf16_bits_to_f64(ep.q[lo:hi]), bf16_bits_to_f64(ep.k[lo:hi]), bf16_bits_to_f64(ep.v[lo:hi]),
+                           cfg.softmax_scale)
+        err = np.abs(got[lo:hi] - ref)
+        worst, total, count = max(worst, float(err.max())), total + float(err.sum()), count + err.size
+        b = int(se.slot_begin[i])
+        cache_ok = cache_ok and np.array_equal(ck[b:b + hi - lo], ep.k[lo:hi]) and np.array_equal(cv[b:b + hi - lo], ep.v[lo:hi])
+    mean = total / max(1, count)
+    return {"workload": f"config 1 ({cfg.name}): every row of the streamed episode against the float64 oracle",
+            "parity": bool(worst <= 2e-2 and mean <= 2e-3 and cache_ok), "max_abs_err": worst, "mean_abs_err": mean,
+            "cache_bit_exact": bool(cache_ok)}
+
+
+def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
+    """One workload through the timed protocol.  steps=None: as many episodes as fit ~0.25 s."""
+    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+    from paper_2509_25762_amd.workload import episode_work
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
     T = len(chunks) - 1
     copies = [StreamedEpisode(ep, chunks, use_workspace=not args.no_workspace) for _ in range(max(1, args.copies))]
+    ncp = len(copies)
     # shared inputs are identical across copies; only the cache slabs and outputs differ
     work = episode_work(cfg, [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
     flops = sum(w["flops"] for w in work)
     kv_bytes = sum(w["kv_read_bytes"] for w in work)
     tot_bytes = sum(w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"] for w in work)
+    fused = not args.two_call
 
     # prompt prefill, once per copy, timed on its own
     torch.cuda.synchronize()
@@ -841,75 +1015,131 @@ def main() -> int:
         se.reset(0)
         se.run_step(0)
     torch.cuda.synchronize()
-    prompt_ms = (time.perf_counter() - t0) * 1e3 / len(copies)
-
-    fused = not args.two_call
+    prompt_ms = (time.perf_counter() - t0) * 1e3 / ncp
 
     def episode(se):
         se.reset(1)
         for t in range(1, T + 1):
             se.run_step(t, fused=fused)
 
-    for w in range(args.warmup):
-        episode(copies[w % len(copies)])
-    torch.cuda.synchronize()
-    # (a full pass of Python's cyclic garbage collector over the imported modules takes tens of
-    # milliseconds of host time, during which nothing is enqueued: none inside the timed region)
+    def interleaved(k):
+        """Episodes k*ncp .. k*ncp+ncp-1 pass by pass over the copies: between two passes of one copy
+        every other copy's pass has run, so the copy's keys have left the last-level cache."""
+        for se in copies:
+            se.reset(1)
+        for t in range(1, T + 1):
+            for se in copies:
+                se.run_step(t, fused=fused)
+
+    def timed_region(run_one, n):
+        """n calls of run_one(i) between two synchronisations; wall milliseconds per call."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            run_one(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / max(1, n)
+
+    # (a full pass of Python's cyclic garbage collector takes tens of milliseconds of host time, during which
+    # nothing is enqueued and the clocks fall back: it runs now, and not again until the timing is over)
     gc.collect()
     gc.disable()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        episode(copies[s % len(copies)])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    gc.enable()
-    ms_per_step = dt * 1e3 / args.steps
+    # warm-up as asked, then keep the GPU loaded until SETTLE_MS of work have run in all, right up to the
+    # synchronisation that opens the timed region
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    done = 0
+    settle_ms = 0.0
+    batch = max(1, warmup)
+    while True:
+        ev0.record()
+        for _ in range(batch):
+            episode(copies[done % ncp])
+            done += 1
+        ev1.record()
+        ev1.synchronize()
+        got = ev0.elapsed_time(ev1)
+        settle_ms += got
+        if settle_ms >= SETTLE_MS:
+            break
+        batch = int(np.ceil((SETTLE_MS - settle_ms) / max(got / batch, 1e-3))) + 1
+    est_ms = got / batch
+    if steps is None:
+        steps = int(min(400, max(8, np.ceil(250.0 / max(est_ms, 1e-3)))))
 
-    # kernel-level timing: the library brackets each of its kernel launches with HIP
-    # events on the launch stream (the stream the kernels run on).  The episodes are
-    # enqueued back to back like the timed ones and the events are read once at the
-    # end, so the kernels are timed at the clock rate the sustained load settles at.
-    prof_steps = min(args.steps, 50)
+    ms_per_step = timed_region(lambda i: episode(copies[(done + i) % ncp]), steps)
+
+    # the same episodes, interleaved pass by pass over the copies (every pass cold)
+    n_groups = max(1, min(steps, 60) // ncp)
+    cold_ms = timed_region(interleaved, n_groups) / ncp
+
+    # kernel-level timing: the library brackets each of its kernel launches with HIP events on the
+    # launch stream (the stream the kernels run on).  The episodes are enqueued back to back like the
+    # timed ones and the events are read once at the end, so the kernels are timed at the clock rate
+    # the sustained load settles at.  Host cost of the calls is collected in the same pass.
+    prof_steps = int(min(steps, 50))
     ob.oppo_profile_enable(True)
     ob.oppo_profile_read()
-    for s in range(prof_steps):
-        episode(copies[s % len(copies)])
-    ms, n = ob.oppo_profile_read()
-    attn_total_ms = ms["attn"] / prof_steps
-    launches_per_step = n["attn"] / prof_steps
-    achieved = flops / (attn_total_ms * 1e-3) / 1e12
-    attn_ms = merge_ms = app_ms = None
-    if args.details:
-        # per pass: the events are read after every pass, which idles the GPU in between
-        attn_ms = np.zeros((prof_steps, T))
-        merge_ms = np.zeros((prof_steps, T))
-        app_ms = np.zeros((prof_steps, T))
-        for s in range(prof_steps):
-            se = copies[s % len(copies)]
-            se.reset(1)
-            for t in range(1, T + 1):
-                se.run_step(t, fused=fused)
-                pm, _ = ob.oppo_profile_read()
-                attn_ms[s, t - 1], merge_ms[s, t - 1], app_ms[s, t - 1] = pm["attn"], pm["merge"], pm["append"]
+    ob.oppo_profile_host()
+    call_us = np.zeros(T)
+    for s_ in range(prof_steps):
+        episode(copies[s_ % ncp])
+    each_ms, each_kind = ob.oppo_profile_read_each()
+    ob.oppo_profile_host()
+    # what a pass costs on the host: every call starts on an empty queue (synchronised first), so that the
+    # time is the call's own and not the wait for room in a queue the host has filled
+    call_us[:] = 0.0
+    host_reps = 3
+    for s_ in range(host_reps):
+        se = copies[s_ % ncp]
+        se.reset(1)
+        for t in range(1, T + 1):
+            torch.cuda.synchronize()
+            h0 = time.perf_counter()
+            se.run_step(t, fused=fused)
+            call_us[t - 1] += (time.perf_counter() - h0) * 1e6 / host_reps
+    host_us, host_calls = ob.oppo_profile_host()
+    ob.oppo_profile_read()
     ob.oppo_profile_enable(False)
+    gc.enable()
+    attn_total_ms = float(each_ms[each_kind == 0].sum()) / prof_steps
+    merge_total_ms = float(each_ms[each_kind == 1].sum()) / prof_steps
+    append_total_ms = float(each_ms[each_kind == 2].sum()) / prof_steps
+    launches_per_step = float(np.sum(each_kind == 0)) / prof_steps
+    # per pass: launches come in call order, a pass = its attention launch(es), then its merge launch(es)
+    pass_attn_ms = np.zeros(T)
+    pass_merge_ms = np.zeros(T)
+    per_pass_ok = False
+    if fused:
+        # walk the launch list: passes alternate attn+ [merge*]; the count of attention launches per pass is
+        # the same in every episode, so the list splits evenly
+        n_attn = int(np.sum(each_kind == 0))
+        if n_attn == prof_steps * T:     # one attention launch per pass (no work list outgrew a launch)
+            t_idx = -1
+            for ms_, kd in zip(each_ms, each_kind):
+                if kd == 0:
+                    t_idx += 1
+                    pass_attn_ms[t_idx % T] += ms_ / prof_steps
+                elif kd == 1 and t_idx >= 0:
+                    pass_merge_ms[t_idx % T] += ms_ / prof_steps
+            per_pass_ok = True
 
     tflops = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (attn_total_ms * 1e-3) / 1e12
     # which roof binds the attention kernel on this workload (classical roofline over the episode's launches)
     bound = "mfma" if flops / (PEAK_BF16_TFLOPS * 1e12) >= tot_bytes / (PEAK_HBM_GBPS * 1e9) else "hbm"
     achieved_gbps = tot_bytes / (attn_total_ms * 1e-3) / 1e9
     t_roof_ms = sum(max(w["flops"] / (PEAK_BF16_TFLOPS * 1e12),
                         (w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"]) / (PEAK_HBM_GBPS * 1e9)) for w in work) * 1e3
-    line = {
-        "metric": "chunked-prefill attn TFLOP/s + KV GB/s, % of MI355X roofline, 1 GPU",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+    traffic, traffic_note = measured_traffic(cfg.index)
+    with_merge_ms = attn_total_ms + merge_total_ms
+    res = {
+        "value": tflops, "ms_per_step": ms_per_step, "steps": int(steps), "settle_ms": settle_ms,
         "config": {"workload": f"config {cfg.index} ({cfg.name}): B={cfg.batch}, Hq/Hkv/D={cfg.num_q_heads}/"
                                f"{cfg.num_kv_heads}/{cfg.head_dim}, C={cfg.chunk}, {T} passes per episode, "
                                f"{int(sum(w['rows'] for w in work))} response rows",
                    "step": ("one streamed episode (one oppo_chunk_step per pass: KV append + chunked-prefill attention)"
                             if fused else "one streamed episode (oppo_kv_append + oppo_chunk_prefill_attn per pass)"),
-                   "cache_copies_rotated": len(copies)},
+                   "cache_copies_rotated": ncp},
         "kv_read_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "total_GBps": tot_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_of_roofline_episode": t_roof_ms / ms_per_step,
@@ -920,26 +1150,112 @@ def main() -> int:
                      "peak": PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBPS,
                      "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
                      "frac": achieved / PEAK_BF16_TFLOPS if bound == "mfma" else achieved_gbps / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.index),
+                     "traffic": traffic, "traffic_note": traffic_note,
                      "algorithmic_bytes_per_launch": sum(w["kv_read_bytes"] + w["qo_bytes"] +
                                                          (w["append_bytes"] if fused else 0) for w in work) / T,
                      "kernel": "attn_fwd_kernel",
-                     "launches_per_step": launches_per_step, "avg_launch_ms": attn_total_ms / launches_per_step},
-        "append_kernel_ms_per_step": ms["append"] / prof_steps,
-        "merge_kernel_ms_per_step": ms["merge"] / prof_steps,
+                     "launches_per_step": launches_per_step, "avg_launch_ms": attn_total_ms / max(launches_per_step, 1e-9),
+                     # the same with the merge kernel's time in the denominator (the cost of the plan that was run)
+                     "achieved_with_merge": (flops / (with_merge_ms * 1e-3) / 1e12) if bound == "mfma"
+                                            else tot_bytes / (with_merge_ms * 1e-3) / 1e9,
+                     "frac_with_merge": (flops / (with_merge_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if bound == "mfma"
+                                        else tot_bytes / (with_merge_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS},
+        "append_kernel_ms_per_step": append_total_ms,
+        "merge_kernel_ms_per_step": merge_total_ms,
+        "pass_cold": {"value": flops / (cold_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": cold_ms,
+                      "kv_read_GBps": kv_bytes / (cold_ms * 1e-3) / 1e9,
+                      "how": f"{ncp} episodes interleaved pass by pass over the cache copies"},
+        "host_us_per_pass": {"library_plan": host_us["plan"] / max(1, host_calls), "library_launch": host_us["launch"] / max(1, host_calls),
+                             "binding_call_wall": float(call_us.sum()) / T,
+                             "kernel_us_per_pass": with_merge_ms * 1e3 / T},
     }
-    if args.details:
-        attn_pass_ms = attn_ms.mean(axis=0)
-        det = {"attn_pass_ms": attn_pass_ms.tolist(), "append_pass_ms": app_ms.mean(axis=0).tolist(),
-               "merge_pass_ms": merge_ms.mean(axis=0).tolist(),
-               "work": work, "ms_per_step": ms_per_step}
-        with open(args.details, "w") as f:
-            json.dump(det, f, indent=1)
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, ep)
+    w0 = work[0]
+    if per_pass_ok:
+        k0 = pass_attn_ms[0]
+        b0 = w0["kv_read_bytes"] + w0["qo_bytes"] + w0["append_bytes"]
+        res["step0"] = {"what": "the first response pass (full batch) on its own, attention kernel time",
+                        "kernel_ms": k0, "tflops": w0["flops"] / (k0 * 1e-3) / 1e12, "total_GBps": b0 / (k0 * 1e-3) / 1e9,
+                        "kv_read_GBps": w0["kv_read_bytes"] / (k0 * 1e-3) / 1e9,
+                        "frac": (w0["flops"] / (k0 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if bound == "mfma"
+                                else b0 / (k0 * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+        res["host_us_per_pass"]["binding_call_wall_by_pass"] = call_us.round(1).tolist()
+        res["host_us_per_pass"]["kernel_us_by_pass"] = ((pass_attn_ms + pass_merge_ms) * 1e3).round(1).tolist()
     else:
-        line["cpu_baseline"] = None
-    print(json.dumps(line))
+        res["step0"] = None
+    if details:
+        det = {"attn_pass_ms": pass_attn_ms.tolist(), "merge_pass_ms": pass_merge_ms.tolist(), "work": work,
+               "ms_per_step": ms_per_step, "call_us": call_us.tolist()}
+        with open(details, "w") as f:
+            json.dump(det, f, indent=1)
+    del copies
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res
+
+
+def traffic_from(args) -> int:
+    """Turns the counter files of rocprofv3 --pmc FETCH_SIZE / --pmc WRITE_SIZE runs of this program into
+    profiles/hbm_traffic.json.  --traffic-from takes a directory holding, per workload N, the csv outputs
+    `cfgN_fetch*counter_collection.csv` and `cfgN_write*counter_collection.csv` of
+        rocprofv3 --pmc FETCH_SIZE  ... -o cfgN_fetch -- python3 bench.py --config N --single --no-cpu-baseline --steps 12 --warmup 4
+        rocprofv3 --pmc WRITE_SIZE  ... -o cfgN_write -- python3 bench.py --config N --single --no-cpu-baseline --steps 12 --warmup 4
+    and, for the calibration, `cal_fetch*` / `cal_write*` of the same two commands with `--config 2 --two-call`
+    (its append kernel is a plain copy of known size).  Counters are KiB per dispatch."""
+    import csv
+    import glob
+    import subprocess
+    from paper_2509_25762_amd.workload import CONFIGS, draw_lengths
+
+    def per_kernel(pattern):
+        files = sorted(glob.glob(os.path.join(args.traffic_from, "**", pattern), recursive=True))
+        if not files:
+            return None
+        acc = {}
+        for fn in files:
+            with open(fn) as f:
+                for row in csv.DictReader(f):
+                    name = row.get("Kernel_Name", "")
+                    val = float(row.get("Counter_Value", 0.0))
+                    key = ("attn" if "attn_fwd_kernel" in name else "append" if "kv_append_kernel" in name else None)
+                    if key:
+                        acc.setdefault(key, []).append(val)
+        return acc
+
+    cal_f, cal_w = per_kernel("cal_fetch*counter_collection.csv"), per_kernel("cal_write*counter_collection.csv")
+    if not cal_f or not cal_w or "append" not in cal_f or "append" not in cal_w:
+        print("bench.py: calibration runs (cal_fetch*, cal_write*) not found", file=sys.stderr)
+        return 2
+    # the largest append launch is the full-batch pass: rows x Hkv x D x 2 bytes for K and again for V
+    c2 = CONFIGS[2]
+    P, R = draw_lengths(c2)
+    rows0 = int(np.minimum(c2.chunk, R).sum())
+    true_kib = 2.0 * rows0 * c2.num_kv_heads * c2.head_dim * 2 / 1024.0
+    f_scale = true_kib / max(cal_f["append"])
+    w_scale = true_kib / max(cal_w["append"])
+    out = {"unit": "bytes per attn_fwd_kernel launch (HBM reads + writes), response-pass launches averaged",
+           "method": "rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (KiB per dispatch), each scaled by what the same counter "
+                     "reads for the append kernel of the full-batch pass of config 2 in a --two-call run (a plain copy of known size)",
+           "fetch_scale": f_scale, "write_scale": w_scale, "source_fingerprint": source_fingerprint(), "configs": {}}
+    try:
+        out["commit"] = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip() or "?"
+    except OSError:
+        out["commit"] = "?"
+    for ci in sorted(CONFIGS):
+        f, w = per_kernel(f"cfg{ci}_fetch*counter_collection.csv"), per_kernel(f"cfg{ci}_write*counter_collection.csv")
+        if not f or not w or "attn" not in f or "attn" not in w:
+            continue
+        T = int(-(-int(draw_lengths(CONFIGS[ci])[1].max()) // CONFIGS[ci].chunk))
+        # the first launches of a run are the prompt prefills (one per cache copy): drop them, keep whole episodes
+        fa, wa = np.array(f["attn"][args.copies:]), np.array(w["attn"][args.copies:])
+        fa, wa = fa[: len(fa) // T * T], wa[: len(wa) // T * T]
+        out["configs"][str(ci)] = {"fetch_KiB": float(fa.mean()), "write_KiB": float(wa.mean()),
+                                   "traffic_bytes_per_launch": float((fa.mean() * f_scale + wa.mean() * w_scale) * 1024.0),
+                                   "launches_averaged": int(len(fa))}
+    os.makedirs(os.path.dirname(TRAFFIC_FILE), exist_ok=True)
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out))
     return 0
 
 

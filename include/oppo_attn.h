@@ -431,6 +431,10 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
  * (host arrays; index 0 = attention kernel, 1 = split-KV merge kernel,
  * 2 = append kernel) and forgets them.  The list of events is shared by all
  * threads (guarded by a lock): a read collects every thread's launches.
+ * oppo_profile_read_each does the same but hands out every launch's own duration
+ * (each_ms[i], milliseconds) and kind (each_kind[i], numbered as above) in launch
+ * order, *n of them; INVALID (after forgetting them all the same) if more than
+ * max_n launches were recorded.
  * oppo_profile_host reports what the attention entry points cost on the host
  * while profiling was enabled, summed since the last read: host_us[0] =
  * microseconds spent planning (cutting the pass into pieces and queues),
@@ -439,6 +443,7 @@ int oppo_plan_debug(const oppo_attn_desc* desc, int32_t B, const int32_t* kv_bef
  */
 int oppo_profile_enable(int on);
 int oppo_profile_read(double* kernel_ms /* [3] */, int32_t* launches /* [3] */);
+int oppo_profile_read_each(double* each_ms /* [max_n] */, int32_t* each_kind /* [max_n] */, int32_t max_n, int32_t* n);
 int oppo_profile_host(double* host_us /* [2] */, int64_t* calls);
 
 /* Reason of the last failing call on this thread ("" if none). */

@@ -31,7 +31,7 @@ OPT_NUM_CUS = 2
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append",
-    "oppo_profile_enable", "oppo_profile_read", "oppo_profile_host", "oppo_chunk_step_noalloc", "oppo_static_scratch_bytes",
+    "oppo_profile_enable", "oppo_profile_read", "oppo_profile_read_each", "oppo_profile_host", "oppo_chunk_step_noalloc", "oppo_static_scratch_bytes",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
@@ -96,6 +96,8 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_step_noalloc.restype = ctypes.c_int
     lib.oppo_static_scratch_bytes.argtypes = []
     lib.oppo_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.oppo_profile_read_each.argtypes = [ctypes.POINTER(ctypes.c_double), i32p, ctypes.c_int32, i32p]
+    lib.oppo_profile_read_each.restype = ctypes.c_int
     lib.oppo_profile_host.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.oppo_profile_host.restype = ctypes.c_int
     lib.oppo_full_prefill_ref.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32, i32p, vp, vp, vp, vp, vp,
@@ -450,6 +452,15 @@ def oppo_profile_read():
     _check(load().oppo_profile_read(ms, n))
     names = ("attn", "merge", "append")
     return {k: ms[i] for i, k in enumerate(names)}, {k: n[i] for i, k in enumerate(names)}
+
+
+def oppo_profile_read_each(max_n: int = 1 << 16):
+    """(ms[n] float64, kind[n] int32: 0 attention, 1 merge, 2 append) of every launch since the last read, in launch order."""
+    ms = np.zeros(max_n, dtype=np.float64)
+    kind = np.zeros(max_n, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(load().oppo_profile_read_each(ms.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), _i32p(kind), max_n, ctypes.byref(n)))
+    return ms[: n.value].copy(), kind[: n.value].copy()
 
 
 def oppo_profile_host():

@@ -974,8 +974,19 @@ int oppo_profile_enable(int on) { return oppo::profile_enable(on); }
 
 int oppo_profile_read(double* kernel_ms, int32_t* launches) {
   if (!kernel_ms || !launches) return fail(OPPO_ERR_INVALID, "null array");
-  const int e = oppo::profile_read(kernel_ms, launches);
+  const int e = oppo::profile_read(kernel_ms, launches, nullptr, nullptr, 0, nullptr);
   if (e) return fail(OPPO_ERR_HIP, "event timing failed: %s", oppo::hip_error_string(e));
+  return OPPO_OK;
+}
+
+int oppo_profile_read_each(double* each_ms, int32_t* each_kind, int32_t max_n, int32_t* n) {
+  if (!each_ms || !each_kind || !n || max_n < 0) return fail(OPPO_ERR_INVALID, "null array or negative size");
+  double ms[3];
+  int32_t launches[3];
+  const int e = oppo::profile_read(ms, launches, each_ms, each_kind, max_n, n);
+  if (e) return fail(OPPO_ERR_HIP, "event timing failed: %s", oppo::hip_error_string(e));
+  if (launches[0] + launches[1] + launches[2] > max_n)
+    return fail(OPPO_ERR_INVALID, "%d launches were recorded, room for %d", launches[0] + launches[1] + launches[2], max_n);
   return OPPO_OK;
 }
 

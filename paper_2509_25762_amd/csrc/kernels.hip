@@ -949,7 +949,11 @@ bool profile_is_on() {
   std::lock_guard<std::mutex> lock(g_prof_mu);
   return g_prof_on;
 }
-int profile_read(double ms[3], int32_t launches[3]) {
+// Waits for the recorded pairs and forgets them.  Sums per kind go to ms / launches; if
+// `each_ms` is given, the first max_each launches' own durations and kinds as well, in
+// launch order (n_each = how many were written).
+int profile_read(double ms[3], int32_t launches[3], double* each_ms, int32_t* each_kind, int32_t max_each,
+                 int32_t* n_each) {
   for (int k = 0; k < 3; ++k) ms[k] = 0.0, launches[k] = 0;
   std::vector<EventPair> pairs;
   {
@@ -957,17 +961,26 @@ int profile_read(double ms[3], int32_t launches[3]) {
     pairs.swap(g_prof_events);
   }
   int rc = 0;
+  int32_t written = 0;
   for (EventPair& p : pairs) {
     if (p.closed) {
       float t = 0.f;
       hipError_t e = hipEventSynchronize(p.b);
       if (e == hipSuccess) e = hipEventElapsedTime(&t, p.a, p.b);
       if (e != hipSuccess) rc = (int)e;
-      else if (p.kind >= 0 && p.kind < 3) ms[p.kind] += t, launches[p.kind] += 1;
+      else if (p.kind >= 0 && p.kind < 3) {
+        ms[p.kind] += t, launches[p.kind] += 1;
+        if (each_ms && written < max_each) {
+          each_ms[written] = t;
+          if (each_kind) each_kind[written] = p.kind;
+          ++written;
+        }
+      }
     }
     (void)hipEventDestroy(p.a);
     (void)hipEventDestroy(p.b);
   }
+  if (n_each) *n_each = written;
   return rc;
 }
 

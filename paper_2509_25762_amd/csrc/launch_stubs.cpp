@@ -63,8 +63,9 @@ int profile_enable(int on) {
   return 0;
 }
 bool profile_is_on() { return g_profile_on != 0; }
-int profile_read(double ms[3], int32_t launches[3]) {
+int profile_read(double ms[3], int32_t launches[3], double*, int32_t*, int32_t, int32_t* n_each) {
   for (int k = 0; k < 3; ++k) ms[k] = 0.0, launches[k] = 0;
+  if (n_each) *n_each = 0;
   return 0;
 }
 

@@ -112,7 +112,9 @@ int static_scratch(void** ptr);
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int profile_enable(int on);
 bool profile_is_on();
-int profile_read(double ms[3], int32_t launches[3]);  // 0 attention, 1 merge, 2 append
+// kinds: 0 attention, 1 merge, 2 append
+int profile_read(double ms[3], int32_t launches[3], double* each_ms, int32_t* each_kind, int32_t max_each,
+                 int32_t* n_each);
 
 // Bytes of one partial slot (all kv-heads): kTileRows rows x (D + 2) floats each.
 inline size_t part_slot_bytes(int Hkv, int D) {
