@@ -23,6 +23,9 @@ exactly):
                     their absolute positions (the published definition; the paper is
                     silent on it), the step before append and attention in the scorer's
                     layers;
+  * projection.py - the layer's fused QKV projection (y = x W^T, columns laid out as query,
+                    key, value heads) and the rotary embedding that follows it: the step
+                    of Alg. 1's prefill that produces what the cache and the attention take;
   * overlap.py    - the timeline of intra-step overlap (Sec. 3.1): when the scorer
                     works on which chunk while the actor decodes the next one, and
                     how much scoring time stays exposed at the end of the step.
@@ -45,7 +48,10 @@ forms (a scorer that keeps up exposes only the last chunk; one that never
 idles ends at gen[0] + sum(score)); the rotary embedding by a hand-worked row
 (tests/golden), the complex-number form through an independent routine, and its
 defining properties (identity at position 0, additivity, scores that depend on
-relative position only).  No function here is "parity unpinned".
+relative position only); the projection by a triple loop on tiny inputs, a hand-worked
+example (tests/golden), selector weights that must copy given input columns into given
+heads (which pins the operand order and the head layout) and linearity.  No function here
+is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
@@ -54,10 +60,12 @@ from .deferral import simulate as simulate_alg1_buffer, dense_descriptor
 from .tuner import ChunkTunerOracle, run_tuner
 from .overlap import timeline as overlap_timeline, sequential_step
 from .rope import rope_rotate, pass_positions
+from .projection import qkv_projection, qkv_projection_rope
 
 __all__ = [
     "bf16_bits_to_f64", "causal_attention", "full_prefill", "attention_row",
     "KVCacheOracle", "CapacityError", "stream_episode", "chunk_schedule", "num_steps",
     "simulate_alg1_buffer", "dense_descriptor", "ChunkTunerOracle", "run_tuner",
     "overlap_timeline", "sequential_step", "rope_rotate", "pass_positions",
+    "qkv_projection", "qkv_projection_rope",
 ]

@@ -745,7 +745,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     // ---- epilogue ---------------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (done.part < 0) {
-      // final rows, turned around in the wave's staging area
+      // final rows, turned around in the wave's staging area.  They (and the appended cache
+      // rows further down) are stored with the non-temporal hint: nothing in this launch reads
+      // them again, and lines that do not linger dirty in the level-2 cache need no write-back
+      // when the kernel ends.
       const float inv = 1.0f / l_tot;
       const int ln = lane_now();
       const uint32_t roff = roff_of(ln), cx = cx_of(ln);
@@ -772,7 +775,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
         for (int k = 0; k < 2 * IPW; ++k) {
           const u32x4 val = *(const __attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(
               area_of(st_area, k) + roff);
-          if (grow[k] >= 0) *(u32x4*)(P.out + (int64_t)grow[k] * D + (ln % NS) * 8 + h * (D / 2)) = val;
+          if (grow[k] >= 0) __builtin_nontemporal_store(val, (u32x4*)(P.out + (int64_t)grow[k] * D + (ln % NS) * 8 + h * (D / 2)));
         }
       }
     } else {
@@ -801,15 +804,15 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       for (int ps = 0; ps < 2; ++ps) {
         const int row = ps * CP_ROWS + cp_row;
         if (row < tokens_of(done)) {
-          *(u32x4*)(P.k + cp_dst(row)) = unpark(2 * ps);
-          *(u32x4*)(P.v + cp_dst(row)) = unpark(2 * ps + 1);
+          __builtin_nontemporal_store(unpark(2 * ps), (u32x4*)(P.k + cp_dst(row)));
+          __builtin_nontemporal_store(unpark(2 * ps + 1), (u32x4*)(P.v + cp_dst(row)));
         }
       }
       for (int row = 2 * CP_ROWS + cp_row; row < tokens_of(done); row += CP_ROWS) {
         const u32x4 a = *(const u32x4*)(P.k_new + cp_src(row));
         const u32x4 b = *(const u32x4*)(P.v_new + cp_src(row));
-        *(u32x4*)(P.k + cp_dst(row)) = a;
-        *(u32x4*)(P.v + cp_dst(row)) = b;
+        __builtin_nontemporal_store(a, (u32x4*)(P.k + cp_dst(row)));
+        __builtin_nontemporal_store(b, (u32x4*)(P.v + cp_dst(row)));
       }
     }
     if (more) q_collect(st_area);
