@@ -515,8 +515,84 @@ def qkv_epilogue_bench(args, cfg, torch, ob) -> int:
     return 0
 
 
+def qkv_proj_bench(args, cfg, torch, ob) -> int:
+    """The layer's fused QKV projection on the workload's first response pass, two ways:
+      fused    oppo_qkv_proj_rope_append: hand-written MFMA GEMM whose epilogue rotates queries and keys and writes
+               keys and values into the cache (the projection's output never exists in memory);
+      library  torch.matmul (the vendor library's GEMM) writing [q | k | v] rows, then oppo_qkv_rope_append over them.
+    hidden = Hq * D (a square attention block, 4096 for the Llama-3-8B shape); synthetic weights ~ N(0, 1/hidden)."""
+    from paper_2509_25762_amd.workload import draw_lengths
+    P, R = draw_lengths(cfg)
+    q_len = np.minimum(cfg.chunk, R).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    rows = int(cu[-1])
+    dev = torch.device("cuda:0")
+    Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+    hidden = Hq * D
+    n_out = (Hq + 2 * Hkv) * D
+    ncopy = max(1, args.copies)
+    slot_begin = np.concatenate([[0], np.cumsum(P.astype(np.int64) + q_len)])
+    xs = [torch.randn((rows, hidden), device=dev, dtype=torch.bfloat16) for _ in range(ncopy)]
+    w = (torch.randn((n_out, hidden), device=dev, dtype=torch.float32) / np.sqrt(hidden)).to(torch.bfloat16)
+    q_outs = [torch.empty((rows, Hq, D), device=dev, dtype=torch.int16) for _ in range(ncopy)]
+    ys = [torch.empty((rows, n_out), device=dev, dtype=torch.bfloat16) for _ in range(ncopy)]
+    caches = []
+    for _ in range(ncopy):
+        ck = torch.zeros((int(slot_begin[-1]), Hkv, D), device=dev, dtype=torch.int16)
+        caches.append(ob.KVCache(ck, torch.zeros_like(ck), slot_begin, P))
+    desc = ob.make_desc(Hq, Hkv, D, cfg.softmax_scale)
+    ws = torch.empty(ob.oppo_qkv_proj_workspace_bytes(desc, rows), dtype=torch.uint8, device=dev)
+    steps, warmup = max(20, args.steps // 4), max(10, args.warmup // 2)
+
+    def fused(i):
+        c = caches[i % ncopy]
+        c.kv_len[:] = P
+        ob.oppo_qkv_proj_rope_append(desc, c, cu, xs[i % ncopy].view(torch.int16), hidden, w.view(torch.int16), q_outs[i % ncopy], ws)
+
+    def library(i):
+        c = caches[i % ncopy]
+        c.kv_len[:] = P
+        torch.matmul(xs[i % ncopy], w.t(), out=ys[i % ncopy])
+        ob.oppo_qkv_rope_append(desc, c, cu, ys[i % ncopy].view(torch.int16).view(rows, Hq + 2 * Hkv, D), q_outs[i % ncopy])
+
+    def gemm_only(i):
+        torch.matmul(xs[i % ncopy], w.t(), out=ys[i % ncopy])
+
+    flops = 2.0 * rows * hidden * n_out
+    res = {}
+    for name, fn in (("fused_projection_rope_append", fused), ("library_gemm_then_rope_append", library), ("library_gemm_alone", gemm_only)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        done, total = 0, 0.0
+        while total < SETTLE_MS:                          # settle the clocks under this very load
+            e0.record()
+            for _ in range(warmup):
+                fn(done)
+                done += 1
+            e1.record()
+            e1.synchronize()
+            total += e0.elapsed_time(e1)
+        e0.record()
+        for i in range(steps):
+            fn(done + i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        res[name] = {"ms": ms, "tflops": flops / (ms * 1e-3) / 1e12, "frac_of_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    f = res["fused_projection_rope_append"]
+    print(json.dumps({"metric": "fused QKV projection with rotary / cache epilogue", "value": f["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": steps, "warmup": warmup, "ms_per_step": f["ms"], "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"config {cfg.index} ({cfg.name}), first response pass: {rows} rows x hidden {hidden} -> "
+                                             f"({Hq} + 2 x {Hkv}) heads x {D}, {ncopy} copies in turn"},
+                      "roofline": {"bound": "mfma", "achieved": f["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": f["frac_of_mfma_peak"], "traffic": None, "kernel": "qkv_proj_kernel"},
+                      "paths": res}))
+    return 0
+
+
 def layer_path_bench(args, cfg, torch, ob) -> int:
-    """The attention side of one scorer layer over the streamed episode, two ways:
+    """The attention side of one scorer layer over the streamed episode, two ways (and, with the layer's QKV
+    projection included, two more: oppo_qkv_proj_rope_append + attention against the vendor library's GEMM +
+    oppo_qkv_rope_append + attention):
       A  oppo_rope in place on the chunk's q and k rows, then oppo_chunk_step (append fused into attention);
       B  oppo_qkv_rope_append over the projection's output rows [q | k | v] (rotated keys and values straight
          into the cache), then oppo_chunk_prefill_attn.
@@ -555,18 +631,55 @@ def layer_path_bench(args, cfg, torch, ob) -> int:
             ob.oppo_qkv_rope_append(se.desc, se.cache, st.cu_q, se.qkv[t], se.q_rot[t])
             ob.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, se.q_rot[t], st.out, se.workspace)
 
+    # with the projection included: hidden rows of every pass (synthetic, hidden = Hq * D) and the layer's weights
+    hidden = cfg.num_q_heads * cfg.head_dim
+    n_out = (cfg.num_q_heads + 2 * cfg.num_kv_heads) * cfg.head_dim
+    dev = torch.device("cuda:0")
+    w = (torch.randn((n_out, hidden), device=dev, dtype=torch.float32) / np.sqrt(hidden)).to(torch.bfloat16)
+    for se in copies:
+        se.x = [torch.randn((int(st.cu_q[-1]), hidden), device=dev, dtype=torch.bfloat16) for st in se.steps]
+        se.y = [torch.empty((int(st.cu_q[-1]), n_out), device=dev, dtype=torch.bfloat16) for st in se.steps]
+    max_rows = max(int(st.cu_q[-1]) for st in copies[0].steps)
+    proj_ws = torch.empty(ob.oppo_qkv_proj_workspace_bytes(copies[0].desc, max_rows), dtype=torch.uint8, device=dev)
+    heads = cfg.num_q_heads + 2 * cfg.num_kv_heads
+
+    def path_c(se):
+        se.reset(1)
+        for t in range(1, T + 1):
+            st = se.steps[t]
+            ob.oppo_qkv_proj_rope_append(se.desc, se.cache, st.cu_q, se.x[t].view(torch.int16), hidden, w.view(torch.int16), se.q_rot[t], proj_ws)
+            ob.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, se.q_rot[t], st.out, se.workspace)
+
+    def path_d(se):
+        se.reset(1)
+        for t in range(1, T + 1):
+            st = se.steps[t]
+            torch.matmul(se.x[t], w.t(), out=se.y[t])
+            ob.oppo_qkv_rope_append(se.desc, se.cache, st.cu_q, se.y[t].view(torch.int16).view(-1, heads, cfg.head_dim), se.q_rot[t])
+            ob.oppo_chunk_prefill_attn(se.desc, se.cache, st.cu_q, se.q_rot[t], st.out, se.workspace)
+
     res = {}
-    for name, fn in (("rope_in_place_then_chunk_step", path_a), ("qkv_epilogue_then_attention", path_b)):
-        for w in range(args.warmup):
-            fn(copies[w % len(copies)])
+    for name, fn in (("rope_in_place_then_chunk_step", path_a), ("qkv_epilogue_then_attention", path_b),
+                     ("fused_projection_then_attention", path_c), ("library_gemm_then_qkv_epilogue_then_attention", path_d)):
+        done, total = 0, 0.0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        while total < SETTLE_MS:
+            e0.record()
+            for _ in range(max(1, args.warmup // 4)):
+                fn(copies[done % len(copies)])
+                done += 1
+            e1.record()
+            e1.synchronize()
+            total += e0.elapsed_time(e1)
+        steps = args.steps if name.startswith(("rope", "qkv")) else max(10, args.steps // 5)
         torch.cuda.synchronize()
         gc.collect()
         gc.disable()
         t0 = time.perf_counter()
-        for s_ in range(args.steps):
+        for s_ in range(steps):
             fn(copies[s_ % len(copies)])
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms = (time.perf_counter() - t0) * 1e3 / steps
         gc.enable()
         res[name] = {"ms_per_episode": ms, "attention_tflops": flops / (ms * 1e-3) / 1e12}
     print(json.dumps({"metric": "attention side of one scorer layer over the streamed episode", "n_gpus": 1, "steps": args.steps,
@@ -857,6 +970,9 @@ def main() -> int:
     ap.add_argument("--qkv-epilogue", action="store_true",
                     help="time oppo_qkv_rope_append (rotary embedding + cache write as one pass over the QKV projection's "
                          "output) on the workload's first response pass")
+    ap.add_argument("--qkv-proj", action="store_true",
+                    help="time the fused QKV projection with its rotary / cache epilogue (oppo_qkv_proj_rope_append) on the "
+                         "workload's first response pass, next to the vendor library's GEMM followed by oppo_qkv_rope_append")
     ap.add_argument("--layer-path", action="store_true",
                     help="the streamed episode with the rotary embedding included, two ways: oppo_rope + oppo_chunk_step, "
                          "and oppo_qkv_rope_append + oppo_chunk_prefill_attn")
@@ -885,7 +1001,7 @@ def main() -> int:
     from paper_2509_25762_amd.workload import CONFIGS, build_episode, episode_work
 
     cfg = CONFIGS[args.config]
-    special = (args.deferral >= 0 or args.chunk_sweep or args.overlap or args.inter_step or args.rope or args.qkv_epilogue
+    special = (args.deferral >= 0 or args.chunk_sweep or args.overlap or args.inter_step or args.rope or args.qkv_epilogue or args.qkv_proj
                or args.layer_path or args.thin_pass or args.steady or args.contention)
     if special:
         if not torch.cuda.is_available():
@@ -906,6 +1022,8 @@ def main() -> int:
         return rope_bench(args, cfg, torch, ob)
     if args.qkv_epilogue:
         return qkv_epilogue_bench(args, cfg, torch, ob)
+    if args.qkv_proj:
+        return qkv_proj_bench(args, cfg, torch, ob)
     if args.layer_path:
         return layer_path_bench(args, cfg, torch, ob)
     if args.thin_pass:

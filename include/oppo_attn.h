@@ -148,6 +148,33 @@ int oppo_qkv_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const
                          void* q_out, double theta_base, void* stream);
 
 /*
+ * The layer's fused QKV projection itself, with the call above as its epilogue: what
+ * the scorer runs on a chunk's hidden rows before the attention (Alg. 1: the scorer's
+ * prefill of the rows that arrived; the paper names no layer internals, this is the
+ * attention block of the decoder-only model families it trains, Sec. 4.1).
+ *     y[m, n] = sum_k x[m, k] * w[n, k]          (fp32 accumulation of bf16 products)
+ * with output column n = head * D + d over [Hq query heads | Hkv key heads | Hkv value
+ * heads]; query and key heads are then rotated as in oppo_rope at the row's position
+ * kv_len[i] + j, on the fp32 sums, and rounded once to bf16; value heads are rounded as
+ * they are.  Queries go to q_out, keys and values straight into the sequence's cache
+ * slab at slot kv_len[i] + j; kv_len advances as in oppo_kv_append; what follows is
+ * oppo_chunk_prefill_attn on q_out.  The projection's output never exists in memory.
+ *   x       : DEVICE bf16 [cu_q[batch]][hidden], rows packed like q.
+ *   w       : DEVICE bf16 [(Hq + 2 Hkv) * D][hidden] (output-major: y = x W^T).
+ *   hidden  : multiple of 64 (otherwise UNSUPPORTED).
+ *   q_out   : DEVICE bf16 [cu_q[batch]][Hq][D].
+ *   workspace: DEVICE, 256-byte aligned, at least oppo_qkv_proj_workspace_bytes(desc,
+ *             cu_q[batch]) bytes (per-row cache slots and rotation angles, written and
+ *             read by this call only); WORKSPACE if missing or smaller.
+ * Errors otherwise as for oppo_qkv_rope_append; a failed call writes nothing and leaves
+ * the lengths untouched.
+ */
+size_t oppo_qkv_proj_workspace_bytes(const oppo_attn_desc* desc, int32_t max_rows);
+int oppo_qkv_proj_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q,
+                              const void* x, int32_t hidden, const void* w, void* q_out, double theta_base,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Chunked-prefill attention (step 2 above).  cache->kv_len is the length AFTER
  * the chunk was appended.  Row j of sequence i (row cu_q[i]+j of q and out,
  * device bf16 [cu_q[B]][Hq][D]) is the token at absolute position

@@ -30,7 +30,7 @@ OPT_NUM_CUS = 2
 
 EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
-    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append",
+    "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append", "oppo_qkv_proj_rope_append", "oppo_qkv_proj_workspace_bytes",
     "oppo_profile_enable", "oppo_profile_read", "oppo_profile_read_each", "oppo_profile_host", "oppo_chunk_step_noalloc", "oppo_static_scratch_bytes",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
@@ -86,6 +86,11 @@ def load() -> ctypes.CDLL:
     lib.oppo_qkv_rope_append.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp,
                                          ctypes.c_double, vp]
     lib.oppo_qkv_rope_append.restype = ctypes.c_int
+    lib.oppo_qkv_proj_rope_append.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, ctypes.c_int32,
+                                              vp, vp, ctypes.c_double, vp, ctypes.c_size_t, vp]
+    lib.oppo_qkv_proj_rope_append.restype = ctypes.c_int
+    lib.oppo_qkv_proj_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int32]
+    lib.oppo_qkv_proj_workspace_bytes.restype = ctypes.c_size_t
     lib.oppo_chunk_prefill_attn.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp,
                                             vp, ctypes.c_size_t, vp]
     lib.oppo_chunk_prefill_attn.restype = ctypes.c_int
@@ -511,6 +516,26 @@ def oppo_qkv_rope_append(desc: AttnDesc, cache: KVCache, cu_q, qkv, q_out, theta
     _need_cache(desc, cache)
     _check(load().oppo_qkv_rope_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(qkv),
                                        _dev_ptr(q_out), float(theta_base), _stream_ptr(stream)))
+
+
+def oppo_qkv_proj_workspace_bytes(desc: AttnDesc, max_rows: int) -> int:
+    return int(load().oppo_qkv_proj_workspace_bytes(ctypes.byref(desc), max_rows))
+
+
+def oppo_qkv_proj_rope_append(desc: AttnDesc, cache: KVCache, cu_q, x, hidden: int, w, q_out, workspace,
+                              theta_base: float = 10000.0, stream=None) -> None:
+    """The fused QKV projection of a pass's hidden rows with the rotary embedding and the cache write as its epilogue."""
+    cu = _i32(cu_q, cache.batch + 1)
+    rows = int(cu[-1])
+    _need(x, rows * hidden * 2, "x")
+    _need(w, (desc.num_q_heads + 2 * desc.num_kv_heads) * desc.head_dim * hidden * 2, "w")
+    _need_rows(desc, cu, q_out=q_out)
+    _need_cache(desc, cache)
+    _need(workspace, 1, "workspace")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().oppo_qkv_proj_rope_append(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(x), hidden,
+                                            _dev_ptr(w), _dev_ptr(q_out), float(theta_base), _dev_ptr(workspace), ws_bytes,
+                                            _stream_ptr(stream)))
 
 
 def oppo_chunk_prefill_attn(desc: AttnDesc, cache: KVCache, cu_q, q, out, workspace=None, stream=None) -> None:

@@ -811,6 +811,59 @@ int oppo_qkv_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const
   return OPPO_OK;
 }
 
+size_t oppo_qkv_proj_workspace_bytes(const oppo_attn_desc* desc, int32_t max_rows) {
+  oppo::LayerShape ls;
+  if (max_rows < 0 || check_desc(desc, &ls) != OPPO_OK) return 0;
+  return oppo::proj_workspace_bytes(ls.D, max_rows);
+}
+
+int oppo_qkv_proj_rope_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32_t* cu_q, const void* x,
+                              int32_t hidden, const void* w, void* q_out, double theta_base, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  rc = check_cache(cache);
+  if (rc) return rc;
+  const int32_t B = cache->batch;
+  rc = check_cu(cu_q, B, "cu_q");
+  if (rc) return rc;
+  if (!(theta_base > 1.0) || !std::isfinite(theta_base))
+    return fail(OPPO_ERR_INVALID, "theta_base must be finite and greater than 1 (got %g)", theta_base);
+  if (hidden < 1) return fail(OPPO_ERR_INVALID, "hidden=%d must be positive", hidden);
+  if (hidden % 64 != 0) return fail(OPPO_ERR_UNSUPPORTED, "hidden=%d is not a multiple of 64", hidden);
+  rc = check_room(cache, cu_q);
+  if (rc) return rc;
+  const int32_t rows = cu_q[B];
+  if (rows == 0) return OPPO_OK;
+  if ((int64_t)rows * hidden > INT32_MAX || (int64_t)rows * ls.Hq * ls.D > INT32_MAX)
+    return fail(OPPO_ERR_UNSUPPORTED, "%d rows x %d columns exceed the 32-bit element index of the kernel", rows,
+                std::max(hidden, ls.Hq * ls.D));
+  if (!cache->k || !cache->v || !x || !w || !q_out) return fail(OPPO_ERR_INVALID, "null device pointer");
+  const size_t need = oppo::proj_workspace_bytes(ls.D, rows);
+  if (!workspace || ((uintptr_t)workspace & 255) != 0)
+    return fail(OPPO_ERR_WORKSPACE, "workspace is null or not 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(OPPO_ERR_WORKSPACE, "workspace has %zu bytes, %zu required for %d rows", workspace_bytes, need, rows);
+  std::vector<oppo::QkvItem> items;
+  for (int32_t i = 0; i < B; ++i) {
+    const int32_t ql = cu_q[i + 1] - cu_q[i];
+    if (ql == 0) continue;
+    oppo::QkvItem it;
+    it.dst_row = cache->slot_begin[i] + cache->kv_len[i];
+    it.src_row = cu_q[i];
+    it.n_tok = ql;
+    it.pos0 = cache->kv_len[i];
+    it.pad_ = 0;
+    items.push_back(it);
+  }
+  int e = oppo::launch_qkv_proj(ls, x, w, hidden, rows, q_out, cache->k, cache->v, items.data(), (int)items.size(),
+                                theta_base, workspace, stream);
+  if (e) return fail(OPPO_ERR_HIP, "projection launch failed: %s", oppo::hip_error_string(e));
+  for (int32_t i = 0; i < B; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
+  return OPPO_OK;
+}
+
 int oppo_chunk_prefill_attn(const oppo_attn_desc* desc, const oppo_kv_cache* cache, const int32_t* cu_q,
                             const void* q, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   oppo::LayerShape ls;

@@ -50,6 +50,16 @@ int launch_qkv_rope_append(const LayerShape&, const void*, void*, void*, void*, 
   return 0;
 }
 
+size_t proj_workspace_bytes(int D, int64_t rows) { return (size_t)rows * (8 + (size_t)(D / 2) * 8); }
+
+int launch_qkv_proj(const LayerShape&, const void*, const void*, int32_t hidden, int32_t rows, void*, void*, void*,
+                    const QkvItem* items, int n_items, double, void* workspace, void*) {
+  if (hidden % 64 != 0 || rows <= 0 || !workspace) return 1;
+  int64_t total = 0;
+  for (int i = 0; i < n_items; ++i) total += items[i].n_tok;
+  return total == rows ? 0 : 1;
+}
+
 const char* hip_error_string(int) { return "launcher stub refused the work list"; }
 
 int static_scratch(void** ptr) {

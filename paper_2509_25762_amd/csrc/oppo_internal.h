@@ -99,6 +99,12 @@ int launch_rope(const LayerShape& ls, void* q, void* k, const RopeItem* items, i
                 void* stream);
 int launch_qkv_rope_append(const LayerShape& ls, const void* qkv, void* q_out, void* cache_k, void* cache_v,
                            const QkvItem* items, int n_items, double theta_base, void* stream);
+// The fused QKV projection with the rotary / cache epilogue (gemm.hip).  workspace holds
+// proj_workspace_bytes(D, rows) bytes of per-row data made by a small kernel of the same call.
+size_t proj_workspace_bytes(int D, int64_t rows);
+int launch_qkv_proj(const LayerShape& ls, const void* x, const void* w, int32_t hidden, int32_t rows, void* q_out,
+                    void* cache_k, void* cache_v, const QkvItem* items, int n_items, double theta_base, void* workspace,
+                    void* stream);
 const char* hip_error_string(int err);
 
 // The built-in scratch buffer of the entry point that allocates nothing: a device array

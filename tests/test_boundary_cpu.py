@@ -469,3 +469,46 @@ def test_options_are_snapshotted_per_call_and_settable_from_threads(lib):
         stop.set()
         th.join()
         ob.oppo_set_option(ob.OPT_SPLIT_KV, 0)
+
+
+def test_projection_validation_leaves_lengths_untouched(lib):
+    desc = _desc()
+    cache = _fake_cache([0, 8, 20], [6, 0])
+    ws = 0x100000
+
+    class Ws:
+        def __init__(self, ptr, n):
+            self.ptr, self.n = ptr, n
+
+        def is_contiguous(self):
+            return True
+
+        def data_ptr(self):
+            return self.ptr
+
+        def numel(self):
+            return self.n
+
+        def element_size(self):
+            return 1
+
+    need = ob.oppo_qkv_proj_workspace_bytes(desc, 2)
+    assert need == 2 * (8 + 64 * 8) and ob.oppo_qkv_proj_workspace_bytes(_desc(D=96), 2) == 0
+    cases = [([0, 3, 6], 128, 10000.0, Ws(ws, 1 << 20), ob.OPPO_ERR_CAPACITY),      # 6 + 3 > 8
+             ([0, 3, 2], 128, 10000.0, Ws(ws, 1 << 20), ob.OPPO_ERR_INVALID),       # decreasing
+             ([0, 1, 2], 100, 10000.0, Ws(ws, 1 << 20), ob.OPPO_ERR_UNSUPPORTED),   # hidden not a multiple of 64
+             ([0, 1, 2], 0, 10000.0, Ws(ws, 1 << 20), ob.OPPO_ERR_INVALID),
+             ([0, 1, 2], 128, 1.0, Ws(ws, 1 << 20), ob.OPPO_ERR_INVALID),           # theta_base must exceed 1
+             ([0, 1, 2], 128, 10000.0, Ws(ws, need - 1), ob.OPPO_ERR_WORKSPACE),
+             ([0, 1, 2], 128, 10000.0, Ws(ws + 1, 1 << 20), ob.OPPO_ERR_WORKSPACE),
+             ([0, 1, 2], 128, 10000.0, None, ob.OPPO_ERR_WORKSPACE)]
+    for cu, hidden, base, w_, code in cases:
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_qkv_proj_rope_append(desc, cache, cu, 0x3000, hidden, 0x4000, 0x5000, w_, base, stream=0)
+        assert e.value.code == code, (cu, hidden, base, code, e.value)
+        assert cache.kv_len.tolist() == [6, 0]
+    with pytest.raises(ob.OppoError) as e:               # rows but no weights
+        ob.oppo_qkv_proj_rope_append(desc, cache, [0, 1, 2], 0x3000, 128, None, 0x5000, Ws(ws, 1 << 20), stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID and cache.kv_len.tolist() == [6, 0]
+    ob.oppo_qkv_proj_rope_append(desc, cache, [0, 0, 0], None, 128, None, None, None, stream=0)   # nobody has rows
+    assert cache.kv_len.tolist() == [6, 0]
