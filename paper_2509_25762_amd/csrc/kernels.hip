@@ -150,7 +150,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NSTAGE = 4;
   constexpr int RPI = 1024 / ROWB;     // tile rows one wave-wide 16-byte load covers
   constexpr int IPW = BN / RPI / 8;    // such loads per wave, per tile, for K and again for V
-  constexpr int KDEPTH = KK;         // K fragments kept in flight (a whole unit ahead)
+  constexpr int KDEPTH = KK / 2;     // K fragments kept in flight (half a unit ahead: four MFMA steps cover the
+                                     // LDS latency several times over, and a whole unit costs 16 more registers)
   constexpr int VDEPTH = DB;         // V^T fragments kept in flight
   static_assert(IPW >= 1 && NT == 512, "tile smaller than the workgroup");
 
