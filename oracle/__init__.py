@@ -26,6 +26,9 @@ exactly):
   * projection.py - the layer's fused QKV projection (y = x W^T, columns laid out as query,
                     key, value heads) and the rotary embedding that follows it: the step
                     of Alg. 1's prefill that produces what the cache and the attention take;
+  * fp8_cache.py  - the cache in 8-bit floating point (OCP E4M3 codes under per-tensor scales, keys
+                    token-major, values in blocks of 64 tokens), its append and the attention
+                    over the values the codes stand for;
   * overlap.py    - the timeline of intra-step overlap (Sec. 3.1): when the scorer
                     works on which chunk while the actor decodes the next one, and
                     how much scoring time stays exposed at the end of the step.
@@ -50,8 +53,10 @@ idles ends at gen[0] + sum(score)); the rotary embedding by a hand-worked row
 defining properties (identity at position 0, additivity, scores that depend on
 relative position only); the projection by a triple loop on tiny inputs, a hand-worked
 example (tests/golden), selector weights that must copy given input columns into given
-heads (which pins the operand order and the head layout) and linearity.  No function here
-is "parity unpinned".
+heads (which pins the operand order and the head layout) and linearity; the 8-bit cache by
+hand-derived codes of the format (tests/golden), the round trip over all 256 codes, an
+independent library conversion, the half-step error bound, its layout written out element by
+element and the streaming invariant through it.  No function here is "parity unpinned".
 """
 from .attention import bf16_bits_to_f64, causal_attention, full_prefill, attention_row
 from .kv_cache import KVCacheOracle, CapacityError, stream_episode
