@@ -246,6 +246,67 @@ int oppo_chunk_step_noalloc(const oppo_attn_desc* desc, oppo_kv_cache* cache,
 size_t oppo_static_scratch_bytes(void);
 
 /*
+ * The KV cache in 8 bits per element.  The scorer re-reads every live sequence's whole
+ * cache at each pass of the streaming loop (Sec. 3.1), so with small chunks a pass is bound
+ * by the bytes of K and V; this variant halves them.  The paper does not say how the cache
+ * is stored; what follows is this library's definition.
+ *   format : OCP FP8 E4M3 (1 sign, 4 exponent bits of bias 7, 3 mantissa bits; no
+ *            infinities; largest finite value 448; subnormals are multiples of 2^-9).
+ *   scales : one positive finite float per tensor (k_scale, v_scale), chosen by the caller
+ *            (e.g. the largest magnitude expected / 448).  A bf16 value x is stored as the
+ *            code nearest (ties to even) to clamp(fl32(x * fl32(1 / scale)), -448, 448);
+ *            a code stands for code_value * scale.  NaN inputs are not supported.
+ *   layout : keys token-major like the 16-bit cache, one byte per element,
+ *            k[slot][Hkv][D]; values in blocks of 64 tokens with the token index fastest,
+ *            v[slot / 64][Hkv][D][slot % 64] (the order in which the second product of
+ *            attention contracts them).  Every slot_begin[i] is a multiple of 64.
+ * Only head_dim 128 is built for attention over this cache; the append also takes 64.
+ */
+typedef struct {
+  void* k;                   /* device bytes [total_slots][Hkv][D]                      */
+  void* v;                   /* device bytes [total_slots / 64][Hkv][D][64]             */
+  const int64_t* slot_begin; /* host [batch+1], non-decreasing multiples of 64         */
+  int32_t* kv_len;           /* host [batch], as in oppo_kv_cache                      */
+  int32_t batch;
+  float k_scale;             /* > 0, finite                                            */
+  float v_scale;             /* > 0, finite                                            */
+} oppo_kv_cache_fp8;
+
+/*
+ * oppo_kv_append into the 8-bit cache: rows of k_new / v_new (device bf16
+ * [cu_q[B]][Hkv][D]) are turned into codes as defined above and written to the slots
+ * slot_begin[i] + kv_len[i] + j.  Of the value blocks, the bytes of the new tokens are
+ * written, the bytes of earlier tokens are kept, and what is left of the last block a
+ * sequence's chunk touches is set to zero bytes (so a block never holds anything but
+ * codes and zeros, whatever the memory held before); no other byte changes.  The codes
+ * of a token do not depend on the chunk it arrived in, so streaming-equivalence
+ * (Sec. 3.1, Eq. 3) holds for them bit for bit.  On success kv_len[i] += q_len_i.
+ * Errors: as oppo_kv_append, and INVALID for scales that are not positive and finite or
+ * a slot_begin entry that is not a multiple of 64.
+ */
+int oppo_kv_append_fp8(const oppo_attn_desc* desc, oppo_kv_cache_fp8* cache,
+                       const int32_t* cu_q /* host [batch+1] */,
+                       const void* k_new, const void* v_new, void* stream);
+
+/*
+ * oppo_chunk_prefill_attn over the 8-bit cache: out = causal attention of the chunk's
+ * queries (device bf16, rows as in cu_q) over the values the cached codes stand for,
+ * out device bf16.  Both matrix products run on the 8-bit matrix instructions with fp32
+ * accumulation: the kernel rounds the queries and the softmax weights to E4M3 on the fly
+ * (the weights relative to a per-row reference, so that they use the format's normal
+ * range); keys and values enter exactly as stored.  The result therefore differs from
+ * exact attention over the stored values by the rounding of queries and weights - a few
+ * percent of a value's magnitude per element for short rows, less for long ones - on top
+ * of the error of storing K and V in 8 bits.  Workspace rules as oppo_chunk_prefill_attn.
+ * Errors: as oppo_chunk_prefill_attn; UNSUPPORTED for head_dim != 128; INVALID for bad
+ * scales or slab starts that are not multiples of 64.
+ */
+int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_fp8* cache,
+                                const int32_t* cu_q /* host [batch+1] */,
+                                const void* q, void* out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One-shot causal prefill of whole sequences, without a cache: the reference
  * side of the streaming-equivalence invariant (Sec. 3.1, Eq. 3) on the device.
  * Sequence i owns rows [cu_seq[i], cu_seq[i+1]) of q/out (device bf16

@@ -79,7 +79,8 @@ def quantize(bits: np.ndarray, scale: float) -> np.ndarray:
     rounded to float32 before it is rounded to 8 bits)."""
     x = (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
     inv = np.float32(1.0) / np.float32(scale)
-    y = (x * inv).astype(np.float32)
+    with np.errstate(over="ignore"):                           # (a product beyond float32 is +-inf, which the clamp takes)
+        y = (x * inv).astype(np.float32)
     return e4m3_encode(np.clip(y, np.float32(-E4M3_MAX), np.float32(E4M3_MAX)))
 
 

@@ -32,6 +32,7 @@ EXPORTS = [
     "oppo_chunk_schedule", "oppo_kv_append", "oppo_chunk_prefill_attn", "oppo_chunk_step", "oppo_full_prefill_ref",
     "oppo_workspace_bytes", "oppo_set_option", "oppo_plan_debug", "oppo_last_error", "oppo_version", "oppo_rope", "oppo_qkv_rope_append", "oppo_qkv_proj_rope_append", "oppo_qkv_proj_workspace_bytes",
     "oppo_profile_enable", "oppo_profile_read", "oppo_profile_read_each", "oppo_profile_host", "oppo_chunk_step_noalloc", "oppo_static_scratch_bytes",
+    "oppo_kv_append_fp8", "oppo_chunk_prefill_attn_fp8",
     "oppo_pool_create", "oppo_pool_destroy", "oppo_pool_acquire", "oppo_pool_release", "oppo_pool_slot_of",
     "oppo_pool_cache", "oppo_pool_pack", "oppo_pool_counts",
     "oppo_sched_create", "oppo_sched_destroy", "oppo_sched_set_delta", "oppo_sched_room", "oppo_sched_add",
@@ -58,6 +59,13 @@ class KVCacheStruct(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("slot_begin", ctypes.POINTER(ctypes.c_int64)),
                 ("kv_len", ctypes.POINTER(ctypes.c_int32)), ("batch", ctypes.c_int32)]
+
+
+class KVCacheFp8Struct(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("slot_begin", ctypes.POINTER(ctypes.c_int64)),
+                ("kv_len", ctypes.POINTER(ctypes.c_int32)), ("batch", ctypes.c_int32),
+                ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 _lib = None
@@ -99,6 +107,11 @@ def load() -> ctypes.CDLL:
     lib.oppo_chunk_step.restype = ctypes.c_int
     lib.oppo_chunk_step_noalloc.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheStruct), i32p, vp, vp, vp, vp, vp]
     lib.oppo_chunk_step_noalloc.restype = ctypes.c_int
+    lib.oppo_kv_append_fp8.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheFp8Struct), i32p, vp, vp, vp]
+    lib.oppo_kv_append_fp8.restype = ctypes.c_int
+    lib.oppo_chunk_prefill_attn_fp8.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(KVCacheFp8Struct), i32p, vp, vp, vp,
+                                                ctypes.c_size_t, vp]
+    lib.oppo_chunk_prefill_attn_fp8.restype = ctypes.c_int
     lib.oppo_static_scratch_bytes.argtypes = []
     lib.oppo_static_scratch_bytes.restype = ctypes.c_size_t
     lib.oppo_profile_read_each.argtypes = [ctypes.POINTER(ctypes.c_double), i32p, ctypes.c_int32, i32p]
@@ -202,7 +215,7 @@ def _need(t, nbytes: int, name: str) -> None:
 
 def _need_cache(desc, cache, name: str = "cache") -> None:
     slots = int(cache.slot_begin[-1]) if len(cache.slot_begin) else 0
-    nbytes = slots * desc.num_kv_heads * desc.head_dim * 2
+    nbytes = slots * desc.num_kv_heads * desc.head_dim * getattr(cache, "element_bytes", 2)
     _need(getattr(cache, "k", None), nbytes, f"{name}.k")
     _need(getattr(cache, "v", None), nbytes, f"{name}.v")
 
@@ -234,6 +247,24 @@ class KVCache:
         self.struct = KVCacheStruct(_dev_ptr(k), _dev_ptr(v),
                                     self.slot_begin.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                                     self.kv_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), self.batch)
+
+
+class KVCacheFp8:
+    """The cache in 8-bit codes: k is a byte tensor [total_slots, Hkv, D], v a byte tensor
+    [total_slots / 64, Hkv, D, 64]; every slab starts on a multiple of 64 slots."""
+    element_bytes = 1
+
+    def __init__(self, k, v, slot_begin, k_scale: float, v_scale: float, kv_len=None):
+        self.k = k
+        self.v = v
+        self.slot_begin = np.ascontiguousarray(slot_begin, dtype=np.int64)
+        self.batch = self.slot_begin.shape[0] - 1
+        self.kv_len = np.zeros(self.batch, dtype=np.int32) if kv_len is None else _i32(kv_len, self.batch).copy()
+        self.k_scale, self.v_scale = float(k_scale), float(v_scale)
+        self.struct = KVCacheFp8Struct(_dev_ptr(k), _dev_ptr(v),
+                                       self.slot_begin.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                       self.kv_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), self.batch,
+                                       self.k_scale, self.v_scale)
 
 
 class SlotPool:
@@ -557,6 +588,24 @@ def oppo_chunk_step(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, 
     _check(load().oppo_chunk_step(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
                                   _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(out), _dev_ptr(workspace), ws_bytes,
                                   _stream_ptr(stream)))
+
+
+def oppo_kv_append_fp8(desc: AttnDesc, cache: KVCacheFp8, cu_q, k_new, v_new, stream=None) -> None:
+    cu = _i32(cu_q, cache.batch + 1)
+    _need_rows(desc, cu, k_new=k_new, v_new=v_new)
+    _need_cache(desc, cache)
+    _check(load().oppo_kv_append_fp8(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(k_new),
+                                     _dev_ptr(v_new), _stream_ptr(stream)))
+
+
+def oppo_chunk_prefill_attn_fp8(desc: AttnDesc, cache: KVCacheFp8, cu_q, q, out, workspace=None, stream=None) -> None:
+    cu = _i32(cu_q, cache.batch + 1)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _need_rows(desc, cu, q=q, out=out)
+    _need_cache(desc, cache)
+    _need(workspace, 1, "workspace")
+    _check(load().oppo_chunk_prefill_attn_fp8(ctypes.byref(desc), ctypes.byref(cache.struct), _i32p(cu), _dev_ptr(q),
+                                              _dev_ptr(out), _dev_ptr(workspace), ws_bytes, _stream_ptr(stream)))
 
 
 def oppo_chunk_step_noalloc(desc: AttnDesc, cache: KVCache, cu_q, q, k_new, v_new, out, stream=None) -> None:

@@ -113,6 +113,29 @@ int check_cache(const oppo_kv_cache* cache) {
   return OPPO_OK;
 }
 
+// The 8-bit cache: the same host arrays (returned as a view of the 16-bit cache's type, for the
+// shared checks), slabs on block boundaries, usable scales.
+int check_cache_fp8(const oppo_kv_cache_fp8* cache, oppo_kv_cache* view) {
+  if (!cache) return fail(OPPO_ERR_INVALID, "cache is null");
+  view->k = cache->k;
+  view->v = cache->v;
+  view->slot_begin = cache->slot_begin;
+  view->kv_len = cache->kv_len;
+  view->batch = cache->batch;
+  const int rc = check_cache(view);
+  if (rc) return rc;
+  for (int32_t i = 0; i <= cache->batch; ++i)
+    if (cache->slot_begin[i] % oppo::kKeyTile != 0)
+      return fail(OPPO_ERR_INVALID, "slot_begin[%d]=%lld is not a multiple of %d", i, (long long)cache->slot_begin[i],
+                  oppo::kKeyTile);
+  if (!(cache->k_scale > 0.0f) || !std::isfinite(cache->k_scale) || !(cache->v_scale > 0.0f) ||
+      !std::isfinite(cache->v_scale))
+    return fail(OPPO_ERR_INVALID, "k_scale and v_scale must be positive and finite");
+  if (!std::isfinite(1.0f / cache->k_scale) || !std::isfinite(1.0f / cache->v_scale))
+    return fail(OPPO_ERR_INVALID, "k_scale or v_scale is too small to invert");
+  return OPPO_OK;
+}
+
 // Every sequence's new rows fit behind what its slab already holds.
 int check_room(const oppo_kv_cache* cache, const int32_t* cu_q) {
   for (int32_t i = 0; i < cache->batch; ++i) {
@@ -745,6 +768,68 @@ int oppo_kv_append(const oppo_attn_desc* desc, oppo_kv_cache* cache, const int32
   if (e) return fail(OPPO_ERR_HIP, "append launch failed: %s", oppo::hip_error_string(e));
   for (int32_t i = 0; i < B; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
   return OPPO_OK;
+}
+
+int oppo_kv_append_fp8(const oppo_attn_desc* desc, oppo_kv_cache_fp8* cache, const int32_t* cu_q, const void* k_new,
+                       const void* v_new, void* stream) {
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  oppo_kv_cache view;
+  rc = check_cache_fp8(cache, &view);
+  if (rc) return rc;
+  const int32_t B = view.batch;
+  rc = check_cu(cu_q, B, "cu_q");
+  if (rc) return rc;
+  rc = check_room(&view, cu_q);
+  if (rc) return rc;
+  if (cu_q[B] == 0) return OPPO_OK;
+  if (!view.k || !view.v || !k_new || !v_new) return fail(OPPO_ERR_INVALID, "null device pointer");
+  std::vector<oppo::AppendItem> items;
+  for (int32_t i = 0; i < B; ++i) {
+    const int32_t ql = cu_q[i + 1] - cu_q[i];
+    if (ql == 0) continue;
+    oppo::AppendItem it;
+    it.dst_row = view.slot_begin[i] + view.kv_len[i];
+    it.src_row = cu_q[i];
+    it.n_tok = ql;
+    items.push_back(it);
+  }
+  const int e = oppo::launch_append_fp8(ls, view.k, view.v, k_new, v_new, 1.0f / cache->k_scale, 1.0f / cache->v_scale,
+                                        items.data(), (int)items.size(), stream);
+  if (e) return fail(OPPO_ERR_HIP, "append launch failed: %s", oppo::hip_error_string(e));
+  for (int32_t i = 0; i < B; ++i) cache->kv_len[i] += cu_q[i + 1] - cu_q[i];
+  return OPPO_OK;
+}
+
+int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_fp8* cache, const int32_t* cu_q,
+                                const void* q, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  const Options opt = options_now();
+  oppo::LayerShape ls;
+  int rc = check_desc(desc, &ls);
+  if (rc) return rc;
+  oppo_kv_cache view;
+  rc = check_cache_fp8(cache, &view);
+  if (rc) return rc;
+  if (ls.D != 128) return fail(OPPO_ERR_UNSUPPORTED, "attention over the 8-bit cache is built for head_dim 128 only");
+  const int32_t B = view.batch;
+  rc = check_cu(cu_q, B, "cu_q");
+  if (rc) return rc;
+  rc = check_workspace(ls, workspace, workspace_bytes);
+  if (rc) return rc;
+  if ((int64_t)cu_q[B] * ls.Hq > INT32_MAX)
+    return fail(OPPO_ERR_UNSUPPORTED, "%d query rows x %d heads exceed the 32-bit row index of the kernel", cu_q[B],
+                ls.Hq);
+  std::vector<SeqView> seqs;
+  rc = views_after_append(&view, cu_q, &seqs);
+  if (rc) return rc;
+  if (seqs.empty()) return OPPO_OK;
+  if (!view.k || !view.v || !q || !out) return fail(OPPO_ERR_INVALID, "null device pointer");
+  // the keys' scale goes into the score scale, the values' into the final normalisation
+  ls.fp8 = 1;
+  ls.c *= cache->k_scale;
+  ls.out_scale = cache->v_scale;
+  return run_attention(opt, ls, seqs, q, view.k, view.v, nullptr, nullptr, out, workspace, workspace_bytes, stream, true);
 }
 
 int oppo_rope(const oppo_attn_desc* desc, int32_t batch, const int32_t* kv_before, const int32_t* cu_q, void* q,

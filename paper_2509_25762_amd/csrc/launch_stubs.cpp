@@ -26,6 +26,7 @@ int launch_attention(const LayerShape& ls, const void*, void*, void*, const void
     if (n < 1 || n > ls.TM) return 1;
     if (a.k_begin < 0 || a.k_begin % kKeyTile != 0 || a.k_end <= a.k_begin || a.k_end > a.pos0 + n) return 1;
     if (a.part >= 0 && !part_o) return 1;
+    if (ls.fp8 && (ls.D != 128 || a.kv_row0 % kKeyTile != 0)) return 1;
   }
   return 0;
 }
@@ -39,6 +40,14 @@ int launch_combine(const LayerShape&, void*, const float* part_o, const float*, 
 
 int launch_append(const LayerShape&, void*, void*, const void*, const void*, const AppendItem* items, int n_items, int,
                   void*) {
+  for (int i = 0; i < n_items; ++i)
+    if (items[i].n_tok < 1 || items[i].dst_row < 0 || items[i].src_row < 0) return 1;
+  return 0;
+}
+
+int launch_append_fp8(const LayerShape& ls, void*, void*, const void*, const void*, float k_inv, float v_inv,
+                      const AppendItem* items, int n_items, void*) {
+  if (!(k_inv > 0.0f) || !(v_inv > 0.0f) || (ls.D != 64 && ls.D != 128)) return 1;
   for (int i = 0; i < n_items; ++i)
     if (items[i].n_tok < 1 || items[i].dst_row < 0 || items[i].src_row < 0) return 1;
   return 0;

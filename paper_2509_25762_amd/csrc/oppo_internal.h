@@ -79,7 +79,9 @@ struct QkvItem {
 struct LayerShape {
   int32_t Hq, Hkv, G, D;
   int32_t TM;       // tokens per query tile = kTileRows / G
-  float c;          // softmax_scale * log2(e)
+  float c;          // softmax_scale * log2(e) (8-bit cache: times the key tensor's scale)
+  float out_scale = 1.0f;   // 8-bit cache: the value tensor's scale
+  int32_t fp8 = 0;          // keys and values are E4M3 codes (values in blocks of 64 tokens)
 };
 
 // Launchers (kernels.hip).  Return a hipError_t as int (0 = success).
@@ -94,6 +96,10 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
                    const CombineItem* items, int n_items, void* stream, bool timed);
 int launch_append(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new,
                   const void* v_new, const AppendItem* items, int n_items, int max_tok, void* stream);
+// Append into a cache of E4M3 codes (keys token-major, values in blocks of 64 tokens, every
+// dst_row's slab starting on a block boundary); k_inv / v_inv = fl32(1 / scale).
+int launch_append_fp8(const LayerShape& ls, void* cache_k, void* cache_v, const void* k_new, const void* v_new,
+                      float k_inv, float v_inv, const AppendItem* items, int n_items, void* stream);
 // q / k null: that array is left alone.  (rope.hip)
 int launch_rope(const LayerShape& ls, void* q, void* k, const RopeItem* items, int n_items, double theta_base,
                 void* stream);

@@ -48,14 +48,12 @@ class StreamedEpisode:
         B = cfg.batch
         n = ep.prompt_len.astype(np.int64) + ep.resp_len
         self.slot_begin = np.zeros(B + 1, dtype=np.int64)
-        np.cumsum(n + slack, out=self.slot_begin[1:])
+        align = self.slot_align
+        np.cumsum((n + slack + align - 1) // align * align, out=self.slot_begin[1:])
         self.q_all = bits_to_device(ep.q, self.device)
         self.k_all = bits_to_device(ep.k, self.device)
         self.v_all = bits_to_device(ep.v, self.device)
-        total = int(self.slot_begin[-1])
-        self.cache_k = torch.full((total, cfg.num_kv_heads, cfg.head_dim), -1, dtype=torch.int16, device=self.device)
-        self.cache_v = torch.full_like(self.cache_k, -1)
-        self.cache = ob.KVCache(self.cache_k, self.cache_v, self.slot_begin)
+        self._make_cache(int(self.slot_begin[-1]))
         self.out_all = torch.zeros_like(self.q_all)
         self.workspace = None
         if use_workspace:
@@ -77,6 +75,14 @@ class StreamedEpisode:
                                                device=self.device)))
             done += q_len
         self.total_done = done
+
+    slot_align = 1   # slabs start on multiples of this many slots
+
+    def _make_cache(self, total: int) -> None:
+        cfg = self.cfg
+        self.cache_k = torch.full((total, cfg.num_kv_heads, cfg.head_dim), -1, dtype=torch.int16, device=self.device)
+        self.cache_v = torch.full_like(self.cache_k, -1)
+        self.cache = ob.KVCache(self.cache_k, self.cache_v, self.slot_begin)
 
     def reset(self, first_step: int = 0) -> None:
         """Rewinds the host lengths to the state before pass `first_step`."""
@@ -109,6 +115,36 @@ class StreamedEpisode:
         ob.oppo_full_prefill_ref(self.desc, cu, self.q_all, self.k_all, self.v_all, out,
                                  self.workspace if workspace is None else workspace)
         return out
+
+
+class StreamedEpisodeFp8(StreamedEpisode):
+    """The same episode through the cache of 8-bit codes (append + attention calls; every unused
+    byte starts as 0xFF).  full_prefill is not available: the one-shot reference has no cache."""
+    slot_align = 64
+
+    def __init__(self, ep: Episode, chunks: Sequence[Sequence[int]], k_scale: float, v_scale: float, **kw):
+        self.k_scale, self.v_scale = float(k_scale), float(v_scale)
+        super().__init__(ep, chunks, **kw)
+
+    def _make_cache(self, total: int) -> None:
+        cfg = self.cfg
+        self.cache_k = torch.full((total, cfg.num_kv_heads, cfg.head_dim), 0xFF, dtype=torch.uint8, device=self.device)
+        self.cache_v = torch.full((total // 64, cfg.num_kv_heads, cfg.head_dim, 64), 0xFF, dtype=torch.uint8,
+                                  device=self.device)
+        self.cache = ob.KVCacheFp8(self.cache_k, self.cache_v, self.slot_begin, self.k_scale, self.v_scale)
+
+    def run_step(self, t: int, stream=None, fused: bool = False) -> None:
+        if fused:
+            raise ValueError("the 8-bit cache has no fused call: append, then attend")
+        s = self.steps[t]
+        ob.oppo_kv_append_fp8(self.desc, self.cache, s.cu_q, s.k, s.v, stream)
+        ob.oppo_chunk_prefill_attn_fp8(self.desc, self.cache, s.cu_q, s.q, s.out, self.workspace, stream)
+
+    def run(self, first_step: int = 0, stream=None, fused: bool = False) -> None:
+        super().run(first_step, stream, fused)
+
+    def full_prefill(self, workspace=None):
+        raise NotImplementedError("no 8-bit one-shot reference")
 
 
 def uniform_chunks(prompt_len, resp_len, C: int) -> List[List[int]]:

@@ -170,6 +170,45 @@ static void abi_errors() {
   CHECK(oppo_workspace_bytes(&d, 0, 0) == 0);
 }
 
+static void fp8_cache_errors() {
+  oppo_attn_desc d{32, 8, 128, 0.1f};
+  int64_t slot_begin[3] = {0, 128, 1344};
+  int32_t kv_len[2] = {100, 0};
+  oppo_kv_cache_fp8 cache{fake(0x1000), fake(0x2000), slot_begin, kv_len, 2, 0.01f, 0.02f};
+  int32_t cu_ok[3] = {0, 20, 1020}, cu_over[3] = {0, 29, 30}, cu_attn[3] = {0, 10, 700};
+  CHECK(oppo_kv_append_fp8(&d, nullptr, cu_ok, fake(1), fake(2), nullptr) == OPPO_ERR_INVALID);
+  CHECK(oppo_kv_append_fp8(&d, &cache, cu_over, fake(1), fake(2), nullptr) == OPPO_ERR_CAPACITY);
+  CHECK(oppo_kv_append_fp8(&d, &cache, cu_ok, fake(1), nullptr, nullptr) == OPPO_ERR_INVALID);
+  oppo_kv_cache_fp8 bad = cache;
+  bad.k_scale = 0.0f;
+  CHECK(oppo_kv_append_fp8(&d, &bad, cu_ok, fake(1), fake(2), nullptr) == OPPO_ERR_INVALID);
+  bad.k_scale = 0.0f / 0.0f;
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &bad, cu_ok, fake(1), fake(2), nullptr, 0, nullptr) == OPPO_ERR_INVALID);
+  bad = cache;
+  bad.v_scale = 1e-42f;   // its reciprocal is not finite
+  CHECK(oppo_kv_append_fp8(&d, &bad, cu_ok, fake(1), fake(2), nullptr) == OPPO_ERR_INVALID);
+  int64_t ragged[3] = {0, 100, 1316};
+  bad = cache;
+  bad.slot_begin = ragged;
+  CHECK(oppo_kv_append_fp8(&d, &bad, cu_ok, fake(1), fake(2), nullptr) == OPPO_ERR_INVALID);
+  CHECK(kv_len[0] == 100 && kv_len[1] == 0);
+  CHECK(oppo_kv_append_fp8(&d, &cache, cu_ok, fake(1), fake(2), nullptr) == OPPO_OK);
+  CHECK(kv_len[0] == 120 && kv_len[1] == 1000);
+  // attention: rows must have been appended; with and without a workspace; head size 128 only
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &cache, cu_ok, fake(1), fake(2), nullptr, 0, nullptr) == OPPO_OK);
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &cache, cu_attn, fake(1), fake(2), fake(0x10000),
+                                    oppo_workspace_bytes(&d, 2, 710), nullptr) == OPPO_OK);
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &cache, cu_attn, fake(1), fake(2), fake(0x10001), 1 << 30, nullptr) == OPPO_ERR_WORKSPACE);
+  int32_t cu_more[3] = {0, 121, 121};
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &cache, cu_more, fake(1), fake(2), nullptr, 0, nullptr) == OPPO_ERR_INVALID);
+  CHECK(oppo_chunk_prefill_attn_fp8(&d, &cache, cu_ok, nullptr, fake(2), nullptr, 0, nullptr) == OPPO_ERR_INVALID);
+  oppo_attn_desc d64{8, 8, 64, 0.1f};
+  CHECK(oppo_chunk_prefill_attn_fp8(&d64, &cache, cu_ok, fake(1), fake(2), nullptr, 0, nullptr) == OPPO_ERR_UNSUPPORTED);
+  int32_t cu_one[3] = {0, 1, 1};
+  CHECK(oppo_kv_append_fp8(&d64, &cache, cu_one, fake(1), fake(2), nullptr) == OPPO_OK);
+  CHECK(kv_len[0] == 121);
+}
+
 static void pool_and_scheduler() {
   std::mt19937_64 rng(7);
   int32_t caps[6] = {100, 50, 400, 50, 0, 1000};
@@ -232,6 +271,7 @@ static void pool_and_scheduler() {
 
 int main() {
   abi_errors();
+  fp8_cache_errors();
   planner_fuzz();
   pool_and_scheduler();
   if (g_failed) {

@@ -25,7 +25,7 @@ def lib():
 
 def test_exports_match_header(lib):
     header = open(os.path.join(ROOT, "include", "oppo_attn.h")).read()
-    declared = set(re.findall(r"\b(oppo_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(oppo_[a-z0-9_]+)\s*\(", header))
     assert declared == set(ob.EXPORTS), declared ^ set(ob.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), f"{name} not exported"
@@ -512,3 +512,63 @@ def test_projection_validation_leaves_lengths_untouched(lib):
     assert e.value.code == ob.OPPO_ERR_INVALID and cache.kv_len.tolist() == [6, 0]
     ob.oppo_qkv_proj_rope_append(desc, cache, [0, 0, 0], None, 128, None, None, None, stream=0)   # nobody has rows
     assert cache.kv_len.tolist() == [6, 0]
+
+
+def test_fp8_cache_validation_leaves_lengths_untouched(lib):
+    """Argument checks of the 8-bit cache's two entry points (no device needed: every call fails
+    before a launch, or has nothing to do)."""
+    desc = _desc()
+
+    def cache(slot_begin=(0, 128, 256), kv_len=(100, 0), ks=0.01, vs=0.02):
+        return ob.KVCacheFp8(0x1000, 0x2000, np.asarray(slot_begin), ks, vs, np.asarray(kv_len))
+
+    c = cache()
+    for cu, code in (([0, 29, 30], ob.OPPO_ERR_CAPACITY), ([0, 3, 2], ob.OPPO_ERR_INVALID)):
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_kv_append_fp8(desc, c, cu, 0x3000, 0x4000, stream=0)
+        assert e.value.code == code
+    for bad in (cache(ks=0.0), cache(vs=-1.0), cache(ks=float("nan")), cache(vs=float("inf")), cache(ks=1e-42),
+                cache(slot_begin=(0, 100, 256)), cache(slot_begin=(0, 128, 250))):
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_kv_append_fp8(desc, bad, [0, 1, 2], 0x3000, 0x4000, stream=0)
+        assert e.value.code == ob.OPPO_ERR_INVALID
+        with pytest.raises(ob.OppoError) as e:
+            ob.oppo_chunk_prefill_attn_fp8(desc, bad, [0, 1, 0 + 1], 0x3000, 0x4000, stream=0)
+        assert e.value.code == ob.OPPO_ERR_INVALID
+        assert bad.kv_len.tolist() == [100, 0]
+    with pytest.raises(ob.OppoError) as e:                       # rows that were never appended
+        ob.oppo_chunk_prefill_attn_fp8(desc, c, [0, 101, 101], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID
+    with pytest.raises(ob.OppoError) as e:                       # attention over the codes: head size 128 only
+        ob.oppo_chunk_prefill_attn_fp8(_desc(Hq=8, Hkv=8, D=64), c, [0, 1, 1], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_UNSUPPORTED
+    assert c.kv_len.tolist() == [100, 0]
+    ob.oppo_kv_append_fp8(desc, c, [0, 0, 0], None, None, stream=0)              # nobody has rows: legal
+    ob.oppo_chunk_prefill_attn_fp8(desc, c, [0, 0, 0], None, None, stream=0)
+
+    class Dev:
+        def __init__(self, n):
+            self.n, self.is_cuda = n, True
+
+        def is_contiguous(self):
+            return True
+
+        def data_ptr(self):
+            return 0x100000
+
+        def numel(self):
+            return self.n
+
+        def element_size(self):
+            return 1
+
+    slab = 256 * 8 * 128                                          # one byte per element
+    ok = ob.KVCacheFp8(Dev(slab), Dev(slab), np.array([0, 128, 256]), 1.0, 1.0, np.array([100, 0]))
+    short = ob.KVCacheFp8(Dev(slab), Dev(slab - 1), np.array([0, 128, 256]), 1.0, 1.0, np.array([100, 0]))
+    kv = Dev(2 * 8 * 128 * 2)
+    with pytest.raises(ValueError, match=r"cache\.v holds"):
+        ob.oppo_kv_append_fp8(desc, short, [0, 1, 2], kv, kv, stream=0)
+    with pytest.raises(ValueError, match="v_new holds"):
+        ob.oppo_kv_append_fp8(desc, ok, [0, 1, 2], kv, Dev(2 * 8 * 128 * 2 - 1), stream=0)
+    with pytest.raises(ValueError, match="out holds"):
+        ob.oppo_chunk_prefill_attn_fp8(desc, ok, [0, 1, 1], Dev(32 * 128 * 2), Dev(32 * 128 * 2 - 2), stream=0)

@@ -1,0 +1,264 @@
+"""GPU parity of the 8-bit KV cache (oppo_kv_append_fp8, oppo_chunk_prefill_attn_fp8) against
+oracle/fp8_cache.py, through the C ABI.
+
+Codes and layout are compared bit for bit, every byte of both arrays (unused bytes must still
+hold the 0xFF they were filled with, the rest of a sequence's last value block must be zero).
+
+The attention is compared with float64 attention over the values the oracle's codes stand for,
+with the queries and softmax weights unrounded.  The kernel rounds both to E4M3 (unit roundoff
+2^-4: at most 6.25 %, about 2.6 % rms per element) before the two 8-bit matrix products, so
+its result differs from the oracle's by
+  * the weights' rounding: independent relative errors of ~2.6 % rms on the weights of a row;
+    over a row whose softmax mass sits on n_eff keys the weighted mean of the values moves by
+    about 0.026 |v| / sqrt(n_eff);
+  * the queries' rounding: a score is a sum of D products, each off by ~2.6 % rms of |q_d k_d|,
+    i.e. by 0.026 |q||k| s / sqrt(D) = 0.026 natural units for the workloads' unit-variance
+    inputs and s = 1/sqrt(D): again an independent ~2.6 % relative error on every weight.
+Together ~3.7 % |v| / sqrt(n_eff) rms.  With |v| ~ 1: rows with a single key are exact (the
+weight cancels), rows with a few keys reach 0.1 in the tail of a million elements (a CPU
+emulation of the two roundings on the small case below gives max 0.10, mean 5.3e-3), and rows
+with hundreds of keys err by a few 1e-3.  Asserted: max abs <= 0.2 and mean abs <= 1e-2
+(the 16-bit path's bounds are 2e-2 and 2e-3).
+"""
+import numpy as np
+import pytest
+
+from oracle import bf16_bits_to_f64, chunk_schedule, num_steps
+from oracle.fp8_cache import Fp8KVCacheOracle
+from paper_2509_25762_amd.workload import CONFIGS, Config, build_episode
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 0.2
+MEAN_ABS = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_25762_amd import binding, episode
+    binding.load()  # fails loudly if the HIP library is not built
+    yield binding, episode, torch
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, 0)
+
+
+def uniform_chunks(P, R, C):
+    steps = [[int(p) for p in P]]
+    for t in range(num_steps(R, C)):
+        steps.append([int(x) for x in chunk_schedule(P, R, C, t)[1]])
+    return steps
+
+
+def oracle_run(ep, chunks, slot_begin, k_scale, v_scale):
+    """The oracle's cache after the same appends, and its outputs at the token rows."""
+    cfg = ep.cfg
+    cache = Fp8KVCacheOracle(slot_begin, cfg.num_kv_heads, cfg.head_dim, k_scale, v_scale, fill=0xFF)
+    out = np.zeros(ep.q.shape, dtype=np.float64)
+    done = np.zeros(cfg.batch, dtype=np.int64)
+    for step in chunks:
+        q_len = np.asarray(step, dtype=np.int64)
+        cu = np.concatenate([[0], np.cumsum(q_len)])
+        rows = np.concatenate([ep.tok_begin[i] + done[i] + np.arange(q_len[i]) for i in range(cfg.batch)]).astype(np.int64)
+        cache.append(cu, ep.k[rows], ep.v[rows])
+        if len(rows):
+            out[rows] = cache.attend(cu, ep.q[rows], cfg.softmax_scale)
+        done += q_len
+    return cache, out
+
+
+def run_gpu(gpu, ep, chunks, k_scale, v_scale, use_workspace=True):
+    binding, episode, torch = gpu
+    se = episode.StreamedEpisodeFp8(ep, chunks, k_scale, v_scale, use_workspace=use_workspace)
+    print(f"fp8 episode: batch {ep.cfg.batch}, {len(chunks)} passes, scales {k_scale:g} {v_scale:g}", flush=True)
+    se.run()
+    torch.cuda.synchronize()
+    return se
+
+
+def check_codes(se, cache):
+    gk = se.cache_k.cpu().numpy()
+    gv = se.cache_v.cpu().numpy()
+    assert gk.shape == cache.k.shape and gv.shape == cache.v.shape
+    bad = np.argwhere(gk != cache.k)
+    assert bad.size == 0, f"{len(bad)} key bytes differ, first at {bad[0]}: {gk[tuple(bad[0])]:#x} vs {cache.k[tuple(bad[0])]:#x}"
+    bad = np.argwhere(gv != cache.v)
+    assert bad.size == 0, f"{len(bad)} value bytes differ, first at {bad[0]}: {gv[tuple(bad[0])]:#x} vs {cache.v[tuple(bad[0])]:#x}"
+    assert np.array_equal(se.cache.kv_len, cache.kv_len)
+
+
+def check_outputs(se, ref, what):
+    got = bf16_bits_to_f64(se.scatter_outputs().cpu().numpy().view(np.uint16))
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - ref)
+    print(f"{what}: max abs {err.max():.3e} mean abs {err.mean():.3e}", flush=True)
+    assert err.max() <= MAX_ABS, f"{what}: max abs {err.max():.4e} at {np.unravel_index(err.argmax(), err.shape)}"
+    assert err.mean() <= MEAN_ABS, f"{what}: mean abs {err.mean():.4e}"
+    return err
+
+
+def amax_scale(bits):
+    return float(np.abs(bf16_bits_to_f64(bits)).max()) / 448.0
+
+
+def d128_cfg(B, Hq, Hkv, C, seed, prompt, resp):
+    return Config(98, "fp8 case", seed, B, Hq, Hkv, 128, C, prompt, resp)
+
+
+@pytest.fixture(scope="module")
+def small_ep():
+    # a ragged batch at the headline layer shape: a few tiles per sequence, ragged tails
+    return build_episode(d128_cfg(6, 8, 2, 48, 77, ("uniform", 5, 150), ("lognormal", 100, 0.8, 1, 260)), threads=2)
+
+
+# --------------------------------------------------------------------------- append: codes, bit for bit
+
+@pytest.mark.parametrize("scales", ["amax", (1.0, 1.0), (1.0 / 256, 1.0 / 300), (8.0, 16.0)])
+@pytest.mark.parametrize("C", [1, 13, 64, 100])
+def test_appended_codes_and_layout_bit_exact(gpu, small_ep, scales, C):
+    ep = small_ep
+    ks, vs = (amax_scale(ep.k), amax_scale(ep.v)) if scales == "amax" else scales
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, C)
+    if C == 1:
+        chunks = chunks[:40]      # the prompt and 39 single-token passes
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    cache, _ = oracle_run_codes_only(ep, chunks, se.slot_begin, ks, vs)
+    check_codes(se, cache)
+
+
+def oracle_run_codes_only(ep, chunks, slot_begin, k_scale, v_scale):
+    cfg = ep.cfg
+    cache = Fp8KVCacheOracle(slot_begin, cfg.num_kv_heads, cfg.head_dim, k_scale, v_scale, fill=0xFF)
+    done = np.zeros(cfg.batch, dtype=np.int64)
+    for step in chunks:
+        q_len = np.asarray(step, dtype=np.int64)
+        cu = np.concatenate([[0], np.cumsum(q_len)])
+        rows = np.concatenate([ep.tok_begin[i] + done[i] + np.arange(q_len[i]) for i in range(cfg.batch)]).astype(np.int64)
+        cache.append(cu, ep.k[rows], ep.v[rows])
+        done += q_len
+    return cache, None
+
+
+def test_every_finite_bf16_value_gets_the_oracles_code(gpu):
+    """All 65280 finite bf16 bit patterns as one sequence's keys and values (head size 64 and
+    128), at three scales: ties, subnormal codes, the clamp and the zeros' signs included."""
+    binding, episode, torch = gpu
+    bits = np.arange(65536, dtype=np.uint32)
+    finite = ((bits >> 7) & 0xFF) != 0xFF
+    bits = bits[finite].astype(np.uint16)
+    from oracle.fp8_cache import quantize
+    for D in (64, 128):
+        n = bits.size // D
+        rows = bits[:n * D].reshape(n, 1, D)
+        rows_v = rows[::-1].copy()
+        for ks, vs in ((1.0, 0.5), (1.0 / 64, 3.0), (0.37, 1.0 / 1000)):
+            desc = binding.make_desc(1, 1, D, 1.0)
+            slots = (n + 63) // 64 * 64
+            ck = torch.full((slots, 1, D), 0xFF, dtype=torch.uint8, device="cuda:0")
+            cv = torch.full((slots // 64, 1, D, 64), 0xFF, dtype=torch.uint8, device="cuda:0")
+            cache = binding.KVCacheFp8(ck, cv, [0, slots], ks, vs)
+            kd = torch.from_numpy(rows.view(np.int16)).to("cuda:0")
+            vd = torch.from_numpy(rows_v.view(np.int16)).to("cuda:0")
+            print(f"all finite bf16 values: D={D} scales {ks:g} {vs:g}", flush=True)
+            binding.oppo_kv_append_fp8(desc, cache, [0, n], kd, vd)
+            torch.cuda.synchronize()
+            want_k = quantize(rows, ks)
+            got_k = ck.cpu().numpy()[:n]
+            assert np.array_equal(got_k, want_k), f"D={D} k_scale={ks}: {(got_k != want_k).sum()} key codes differ"
+            want_v = np.zeros((slots, 1, D), dtype=np.uint8)
+            want_v[:n] = quantize(rows_v, vs)
+            got_v = cv.cpu().numpy().transpose(0, 3, 1, 2).reshape(slots, 1, D)
+            assert np.array_equal(got_v, want_v), f"D={D} v_scale={vs}: {(got_v != want_v).sum()} value codes differ"
+
+
+# --------------------------------------------------------------------------- attention
+
+@pytest.mark.parametrize("C", [7, 48, 128])
+def test_attention_over_the_codes_small(gpu, small_ep, C):
+    ep = small_ep
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, C)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    cache, ref = oracle_run(ep, chunks, se.slot_begin, ks, vs)
+    check_codes(se, cache)
+    check_outputs(se, ref, f"fp8 small C={C}")
+
+
+def test_attention_scales_enter_exactly(gpu, small_ep):
+    """Scales that are powers of two change neither the codes' mantissas nor, therefore, what
+    the kernel computes: the outputs of two such runs agree up to the bf16 rounding of the result."""
+    binding, episode, torch = gpu
+    ep = small_ep
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, 48)
+    a = run_gpu(gpu, ep, chunks, 1.0 / 32, 1.0 / 32)
+    b = run_gpu(gpu, ep, chunks, 1.0 / 64, 1.0 / 16)
+    oa = bf16_bits_to_f64(a.scatter_outputs().cpu().numpy().view(np.uint16))
+    ob_ = bf16_bits_to_f64(b.scatter_outputs().cpu().numpy().view(np.uint16))
+    # (values at 1/16 keep one bit less below 2^-6 * 2^-4: tiny differences only)
+    assert np.abs(oa - ob_).max() <= 2e-2
+
+
+def test_attention_with_split_key_ranges_and_without_workspace(gpu):
+    """Few long sequences: the planner cuts their key ranges into pieces merged by the second
+    kernel (the value scale then enters in the merge).  The same run without a workspace
+    must agree with the oracle as well."""
+    binding, episode, torch = gpu
+    ep = build_episode(d128_cfg(2, 8, 2, 64, 5, ("uniform", 900, 1400), ("lognormal", 200, 0.5, 100, 300)), threads=2)
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, 64)
+    ref = None
+    for ws in (True, False):
+        se = run_gpu(gpu, ep, chunks, ks, vs, use_workspace=ws)
+        if ref is None:
+            cache, ref = oracle_run(ep, chunks, se.slot_begin, ks, vs)
+        check_codes(se, cache)
+        check_outputs(se, ref, f"fp8 long workspace={ws}")
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, 1)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    binding.oppo_set_option(binding.OPT_SPLIT_KV, 0)
+    check_outputs(se, ref, "fp8 long forced split")
+
+
+def test_attention_dominant_early_key_and_single_key_rows(gpu):
+    """One key far above the rest early in the row (the reference value moves once and is then
+    held while the weights of later keys are small), and first rows that see one key only.
+    The queries' rounding moves a score in proportion to |k|, so a key scaled up sixfold would
+    take six times the error budget derived above; the queries of this case are therefore put
+    on the E4M3 grid beforehand (the kernel's rounding of them is then exact) and what remains
+    is the weights' rounding alone, whatever the keys' magnitude."""
+    binding, episode, torch = gpu
+    from oracle.fp8_cache import e4m3_decode, e4m3_encode
+    from paper_2509_25762_amd.workload import f32_to_bf16_bits
+    ep = build_episode(d128_cfg(3, 4, 1, 32, 9, ("fixed", 1), ("fixed", 200)), threads=2)
+    k = bf16_bits_to_f64(ep.k)
+    for i in range(ep.cfg.batch):
+        k[int(ep.tok_begin[i]) + 3] *= 6.0          # key 3 of every sequence dominates many rows
+    ep.k[...] = f32_to_bf16_bits(k.astype(np.float32))
+    q = bf16_bits_to_f64(ep.q).astype(np.float32)
+    ep.q[...] = f32_to_bf16_bits(e4m3_decode(e4m3_encode(q)).astype(np.float32))   # (exact in bf16)
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, 32)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    cache, ref = oracle_run(ep, chunks, se.slot_begin, ks, vs)
+    check_codes(se, cache)
+    err = check_outputs(se, ref, "fp8 dominant key")
+    # a sequence's first row sees one key: softmax weight 1, the output is that value's code times the scale
+    for i in range(ep.cfg.batch):
+        assert err[int(ep.tok_begin[i])].max() <= 2.0 ** -8 * np.abs(ref[int(ep.tok_begin[i])]).max() + 1e-6
+
+
+def test_tiny_config_through_the_8_bit_cache_is_refused_for_head_size_64(gpu):
+    binding, episode, torch = gpu
+    ep = build_episode(CONFIGS[1], threads=2)
+    assert ep.cfg.head_dim == 64
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, 32)[:1]
+    se = episode.StreamedEpisodeFp8(ep, chunks, 1.0, 1.0)
+    s = se.steps[0]
+    binding.oppo_kv_append_fp8(se.desc, se.cache, s.cu_q, s.k, s.v)     # the append takes head size 64
+    with pytest.raises(binding.OppoError) as e:
+        binding.oppo_chunk_prefill_attn_fp8(se.desc, se.cache, s.cu_q, s.q, s.out, se.workspace)
+    assert e.value.code == binding.OPPO_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    cache, _ = oracle_run_codes_only(ep, chunks, se.slot_begin, 1.0, 1.0)
+    check_codes(se, cache)
