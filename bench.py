@@ -44,6 +44,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 SETTLE_MS = 200.0            # load the GPU has seen before a timed region starts, at least
 # HBM bytes per attention launch (reads + writes) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by
@@ -988,6 +989,9 @@ def main() -> int:
     ap.add_argument("--single", action="store_true", help="only the workload named by --config, no per_config block")
     ap.add_argument("--traffic-from", type=str, default="", metavar="DIR",
                     help="no GPU work: read rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE csv files from DIR and write profiles/hbm_traffic.json")
+    ap.add_argument("--fp8-cache", action="store_true",
+                    help="study: the workload of --config (head size 128) through the 16-bit cache (append + attention "
+                         "calls) and through the cache of 8-bit codes, same protocol, one JSON line")
     ap.add_argument("--two-call", action="store_true",
                     help="oppo_kv_append + oppo_chunk_prefill_attn per pass instead of the fused oppo_chunk_step")
     args = ap.parse_args()
@@ -1034,6 +1038,8 @@ def main() -> int:
         return contention_study(args, cfg, torch, ob)
     if args.traffic_from:
         return traffic_from(args)
+    if args.fp8_cache:
+        return fp8_cache_bench(args, cfg, torch, ob)
     threads = min(16, len(os.sched_getaffinity(0)))
     ep = build_episode(cfg, threads=threads)
     # the oracle first: its process pool forks, which has to happen before this process touches the GPU
@@ -1085,6 +1091,28 @@ def main() -> int:
     return 0
 
 
+def fp8_cache_bench(args, cfg, torch, ob) -> int:
+    """The same workload through the 16-bit cache and through the 8-bit one (both as append + attention)."""
+    from paper_2509_25762_amd.workload import build_episode
+    if cfg.head_dim != 128:
+        print("bench.py: the 8-bit cache is built for head size 128", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ob.load()
+    ep = build_episode(cfg, threads=min(16, len(os.sched_getaffinity(0))))
+    args.two_call = True
+    out = {"metric": "chunked-prefill attention over a 16-bit and an 8-bit KV cache, 1 GPU", "n_gpus": 1, "data": "synthetic"}
+    for name, fp8 in (("bf16_cache", False), ("fp8_cache", True)):
+        r = measure_workload(cfg, ep, args, torch, ob, steps=None, warmup=3, fp8=fp8)
+        out[name] = {k: r[k] for k in ("value", "ms_per_step", "steps", "kv_read_GBps", "total_GBps", "roofline",
+                                       "append_kernel_ms_per_step", "merge_kernel_ms_per_step", "pass_cold", "config")}
+    out["speedup_episode"] = out["bf16_cache"]["ms_per_step"] / out["fp8_cache"]["ms_per_step"]
+    print(json.dumps(out))
+    return 0
+
+
 def tiny_parity(cfg, ep, torch, ob):
     """The tiny workload streamed through the library and compared, every row, with the float64
     oracle's one-shot prefill (tolerance of the parity tests); the cache bit for bit."""
@@ -1111,20 +1139,32 @@ def tiny_parity(cfg, ep, torch, ob):
             "cache_bit_exact": bool(cache_ok)}
 
 
-def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
-    """One workload through the timed protocol.  steps=None: as many episodes as fit ~0.25 s."""
-    from paper_2509_25762_amd.episode import StreamedEpisode, uniform_chunks
+def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details="", fp8=False):
+    """One workload through the timed protocol.  steps=None: as many episodes as fit ~0.25 s.
+    fp8: through the cache of 8-bit codes (append + attention calls; scales = largest magnitude / 448)."""
+    from paper_2509_25762_amd.episode import StreamedEpisode, StreamedEpisodeFp8, uniform_chunks
     from paper_2509_25762_amd.workload import episode_work
     chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
     T = len(chunks) - 1
-    copies = [StreamedEpisode(ep, chunks, use_workspace=not args.no_workspace) for _ in range(max(1, args.copies))]
+    if fp8:
+        def amax(bits):
+            return float(np.abs((bits.astype(np.uint32) << np.uint32(16)).view(np.float32)).max())
+        ks, vs = amax(ep.k) / 448.0, amax(ep.v) / 448.0
+        copies = [StreamedEpisodeFp8(ep, chunks, ks, vs, use_workspace=not args.no_workspace) for _ in range(max(1, args.copies))]
+    else:
+        copies = [StreamedEpisode(ep, chunks, use_workspace=not args.no_workspace) for _ in range(max(1, args.copies))]
     ncp = len(copies)
     # shared inputs are identical across copies; only the cache slabs and outputs differ
     work = episode_work(cfg, [(s.kv_before, s.q_len) for s in copies[0].steps[1:]])
+    if fp8:
+        for w in work:
+            w["kv_read_bytes"] *= 0.5            # one byte per cached element
+            w["append_bytes"] *= 0.75            # 16-bit rows in, 8-bit codes out
     flops = sum(w["flops"] for w in work)
     kv_bytes = sum(w["kv_read_bytes"] for w in work)
     tot_bytes = sum(w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"] for w in work)
-    fused = not args.two_call
+    fused = not args.two_call and not fp8
+    peak_tflops = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
 
     # prompt prefill, once per copy, timed on its own
     torch.cuda.synchronize()
@@ -1244,11 +1284,11 @@ def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (attn_total_ms * 1e-3) / 1e12
     # which roof binds the attention kernel on this workload (classical roofline over the episode's launches)
-    bound = "mfma" if flops / (PEAK_BF16_TFLOPS * 1e12) >= tot_bytes / (PEAK_HBM_GBPS * 1e9) else "hbm"
+    bound = "mfma" if flops / (peak_tflops * 1e12) >= tot_bytes / (PEAK_HBM_GBPS * 1e9) else "hbm"
     achieved_gbps = tot_bytes / (attn_total_ms * 1e-3) / 1e9
-    t_roof_ms = sum(max(w["flops"] / (PEAK_BF16_TFLOPS * 1e12),
+    t_roof_ms = sum(max(w["flops"] / (peak_tflops * 1e12),
                         (w["kv_read_bytes"] + w["qo_bytes"] + w["append_bytes"]) / (PEAK_HBM_GBPS * 1e9)) for w in work) * 1e3
-    traffic, traffic_note = measured_traffic(cfg.index)
+    traffic, traffic_note = (None, "no counter run on record for the 8-bit variant") if fp8 else measured_traffic(cfg.index)
     with_merge_ms = attn_total_ms + merge_total_ms
     res = {
         "value": tflops, "ms_per_step": ms_per_step, "steps": int(steps), "settle_ms": settle_ms,
@@ -1256,18 +1296,19 @@ def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
                                f"{cfg.num_kv_heads}/{cfg.head_dim}, C={cfg.chunk}, {T} passes per episode, "
                                f"{int(sum(w['rows'] for w in work))} response rows",
                    "step": ("one streamed episode (one oppo_chunk_step per pass: KV append + chunked-prefill attention)"
-                            if fused else "one streamed episode (oppo_kv_append + oppo_chunk_prefill_attn per pass)"),
+                            if fused else "one streamed episode (oppo_kv_append_fp8 + oppo_chunk_prefill_attn_fp8 per pass)"
+                            if fp8 else "one streamed episode (oppo_kv_append + oppo_chunk_prefill_attn per pass)"),
                    "cache_copies_rotated": ncp},
         "kv_read_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "total_GBps": tot_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_of_roofline_episode": t_roof_ms / ms_per_step,
-        "frac_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "frac_mfma_peak": tflops / peak_tflops,
         "frac_hbm_peak": tot_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBPS,
         "prompt_prefill_ms": prompt_ms,
         "roofline": {"bound": bound, "achieved": achieved if bound == "mfma" else achieved_gbps,
-                     "peak": PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBPS,
+                     "peak": peak_tflops if bound == "mfma" else PEAK_HBM_GBPS,
                      "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS if bound == "mfma" else achieved_gbps / PEAK_HBM_GBPS,
+                     "frac": achieved / peak_tflops if bound == "mfma" else achieved_gbps / PEAK_HBM_GBPS,
                      "traffic": traffic, "traffic_note": traffic_note,
                      "algorithmic_bytes_per_launch": sum(w["kv_read_bytes"] + w["qo_bytes"] +
                                                          (w["append_bytes"] if fused else 0) for w in work) / T,
@@ -1276,7 +1317,7 @@ def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
                      # the same with the merge kernel's time in the denominator (the cost of the plan that was run)
                      "achieved_with_merge": (flops / (with_merge_ms * 1e-3) / 1e12) if bound == "mfma"
                                             else tot_bytes / (with_merge_ms * 1e-3) / 1e9,
-                     "frac_with_merge": (flops / (with_merge_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if bound == "mfma"
+                     "frac_with_merge": (flops / (with_merge_ms * 1e-3) / 1e12 / peak_tflops) if bound == "mfma"
                                         else tot_bytes / (with_merge_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS},
         "append_kernel_ms_per_step": append_total_ms,
         "merge_kernel_ms_per_step": merge_total_ms,
@@ -1294,7 +1335,7 @@ def measure_workload(cfg, ep, args, torch, ob, steps, warmup, details=""):
         res["step0"] = {"what": "the first response pass (full batch) on its own, attention kernel time",
                         "kernel_ms": k0, "tflops": w0["flops"] / (k0 * 1e-3) / 1e12, "total_GBps": b0 / (k0 * 1e-3) / 1e9,
                         "kv_read_GBps": w0["kv_read_bytes"] / (k0 * 1e-3) / 1e9,
-                        "frac": (w0["flops"] / (k0 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if bound == "mfma"
+                        "frac": (w0["flops"] / (k0 * 1e-3) / 1e12 / peak_tflops) if bound == "mfma"
                                 else b0 / (k0 * 1e-3) / 1e9 / PEAK_HBM_GBPS}
         res["host_us_per_pass"]["binding_call_wall_by_pass"] = call_us.round(1).tolist()
         res["host_us_per_pass"]["kernel_us_by_pass"] = ((pass_attn_ms + pass_merge_ms) * 1e3).round(1).tolist()

@@ -1025,7 +1025,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams P) {
 // to clamp(fl32(x * inv_scale), -448, 448).  Keys keep the token-major order, one byte per
 // element; values go into blocks of 64 tokens, [block][kv-head][element][token % 64], and what is
 // left of the last block a run touches is filled with zero bytes.
-// grid = (items, 64-token blocks the longest run touches, kv-heads); 4 * D threads.
+// grid = (items, 64-token blocks the longest run touches, kv-heads); 2 * D threads.
 struct Append8Params {
   uint8_t* cache_k;
   uint8_t* cache_v;
@@ -1043,9 +1043,12 @@ __device__ __forceinline__ float code_range(uint32_t bf16_bits, float inv) {
 }
 
 template <int D>
-__global__ __launch_bounds__(4 * D) void kv_append_fp8_kernel(const Append8Params P) {
-  constexpr int NT = 4 * D;
+__global__ __launch_bounds__(2 * D) void kv_append_fp8_kernel(const Append8Params P) {
+  constexpr int NT = 2 * D;       // one thread per (4 tokens, 8 elements) of a 64-token block
   constexpr int BLK = kKeyTile;   // tokens per value block
+  constexpr int NG = D / 8;       // 16-byte granules of a bf16 row of one kv-head
+  constexpr int LROW = BLK + 4;   // bytes per element row of the transposed block in LDS (padded: 17 dwords)
+  __shared__ __attribute__((aligned(16))) uint32_t vt[D * LROW / 4];
   const AppendItem it = P.items[blockIdx.x];
   const int64_t first = it.dst_row, end = it.dst_row + it.n_tok;   // the run's slots
   const int64_t blk = first / BLK + blockIdx.y;
@@ -1055,10 +1058,10 @@ __global__ __launch_bounds__(4 * D) void kv_append_fp8_kernel(const Append8Param
   const int64_t hi = end < (blk + 1) * BLK ? end : (blk + 1) * BLK;
   const int64_t row_stride = (int64_t)P.Hkv * D;
   // keys: 8 elements (16 bytes in, 8 bytes out) per thread and step
-  const int n8 = (int)(hi - lo) * (D / 8);
+  const int n8 = (int)(hi - lo) * NG;
   for (int idx = threadIdx.x; idx < n8; idx += NT) {
-    const int64_t slot = lo + idx / (D / 8);
-    const int g = idx % (D / 8);
+    const int64_t slot = lo + idx / NG;
+    const int g = idx % NG;
     const u32x4 raw = *(const u32x4*)(P.k_new + (it.src_row + (slot - first)) * row_stride + kvh * D + g * 8);
     int w0 = 0, w1 = 0;
     w0 = __builtin_amdgcn_cvt_pk_fp8_f32(code_range(raw[0] & 0xffffu, P.k_inv), code_range(raw[0] >> 16, P.k_inv), w0, false);
@@ -1067,34 +1070,57 @@ __global__ __launch_bounds__(4 * D) void kv_append_fp8_kernel(const Append8Param
     w1 = __builtin_amdgcn_cvt_pk_fp8_f32(code_range(raw[3] & 0xffffu, P.k_inv), code_range(raw[3] >> 16, P.k_inv), w1, true);
     *(u32x2*)(P.cache_k + slot * row_stride + kvh * D + g * 8) = u32x2{(uint32_t)w0, (uint32_t)w1};
   }
-  // values: thread (d, quarter) makes the 16 bytes of element d, tokens 16 * quarter .. of the
-  // block (a wave writes 1 KiB in one piece).  Bytes of tokens before the run are kept, bytes
-  // of tokens behind it are zero.
-  const int d = threadIdx.x / 4, tq = threadIdx.x % 4;
-  const int64_t s0 = blk * BLK + tq * 16;
-  if (s0 + 16 <= lo) return;   // all of it was there before
-  uint8_t* dst = P.cache_v + ((blk * P.Hkv + kvh) * D + d) * BLK + tq * 16;
-  u32x4 res = {0u, 0u, 0u, 0u};
-  if (s0 < lo) res = *(const u32x4*)dst;
-  const uint16_t* src = P.v_new + (it.src_row - first) * row_stride + kvh * D + d;   // + slot * row_stride
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    float x[4];
+  // values, step 1: thread (quad, granule) reads 8 elements of the block's tokens 4 * quad .. + 3
+  // (whole 16-byte pieces of the token rows), turns each element's four tokens into one 32-bit word
+  // of codes (tokens outside the run: zero) and puts it into the transposed block in LDS
+  {
+    const int quad = threadIdx.x / NG, g = threadIdx.x % NG;
+    const int64_t s0 = blk * BLK + 4 * quad;
+    u32x4 raw[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int64_t slot = s0 + 4 * j + e;
-      x[e] = (slot >= lo && slot < hi) ? code_range(src[slot * row_stride], P.v_inv) : 0.0f;
+      const int64_t slot = s0 + e;
+      raw[e] = u32x4{0u, 0u, 0u, 0u};
+      if (slot >= lo && slot < hi)
+        raw[e] = *(const u32x4*)(P.v_new + (it.src_row + (slot - first)) * row_stride + kvh * D + g * 8);
     }
-    int w = 0;
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
-    uint32_t keep = 0u;   // bytes of tokens before the run
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (s0 + 4 * j + e < lo) keep |= 0xffu << (8 * e);
-    res[j] = (res[j] & keep) | ((uint32_t)w & ~keep);
+    for (int j = 0; j < 8; ++j) {
+      float x[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = code_range((j & 1) ? raw[e][j / 2] >> 16 : raw[e][j / 2] & 0xffffu, P.v_inv);
+      int w = 0;
+      w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
+      w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
+      vt[((8 * g + j) * LROW) / 4 + quad] = (uint32_t)w;
+    }
   }
-  *(u32x4*)dst = res;
+  __syncthreads();
+  // step 2: 16-byte pieces (element d, tokens 16 * tq ..) go out, a wave writing 1 KiB in one piece.
+  // Bytes of tokens before the run are kept, bytes of tokens behind it are zero.
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int piece = threadIdx.x + i * NT;
+    const int d = piece / 4, tq = piece % 4;
+    const int64_t s0 = blk * BLK + tq * 16;
+    if (s0 + 16 <= lo) continue;   // all of it was there before
+    uint8_t* dst = P.cache_v + ((blk * P.Hkv + kvh) * D + d) * BLK + tq * 16;
+    u32x4 res;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) res[j] = vt[(d * LROW) / 4 + tq * 4 + j];
+    if (s0 < lo) {
+      const u32x4 old = *(const u32x4*)dst;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        uint32_t keep = 0u;   // bytes of tokens before the run
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (s0 + 4 * j + e < lo) keep |= 0xffu << (8 * e);
+        res[j] = (old[j] & keep) | (res[j] & ~keep);
+      }
+    }
+    *(u32x4*)dst = res;
+  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -1337,8 +1363,8 @@ int launch_append_fp8(const LayerShape& ls, void* cache_k, void* cache_v, const 
     if (blocks > 65535) return (int)hipErrorInvalidValue;
     dim3 grid((unsigned)n, (unsigned)blocks, (unsigned)ls.Hkv);
     const int pair = prof_begin(2, st);
-    if (ls.D == 128) hipLaunchKernelGGL(kv_append_fp8_kernel<128>, grid, dim3(512), 0, st, P);
-    else hipLaunchKernelGGL(kv_append_fp8_kernel<64>, grid, dim3(256), 0, st, P);
+    if (ls.D == 128) hipLaunchKernelGGL(kv_append_fp8_kernel<128>, grid, dim3(256), 0, st, P);
+    else hipLaunchKernelGGL(kv_append_fp8_kernel<64>, grid, dim3(128), 0, st, P);
     prof_end(pair, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
