@@ -32,6 +32,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 struct AttnParams {
   const uint16_t* q;
@@ -45,6 +47,8 @@ struct AttnParams {
   int32_t Hq, Hkv, G, TM;
   float c;
   float out_scale;     // 8-bit cache: the value tensor's scale (the output is the weighted mean of codes times it)
+  float q_mult;        // 8-bit cache: c * 2^k, what the queries are multiplied by before they are rounded to E4M3
+  int32_t q_scale_byte;   // ... and the E8M0 code of 2^-k (127 - k), the query operand's scale in the MFMA
   int32_t n_queues;
   uint32_t g_magic;    // ceil(2^16 / G): r / G == (r * g_magic) >> 16 for the rows r < 256 of a packed tile
   uint16_t first[kMaxQueues + 1];   // queue j runs pieces first[j] .. first[j+1]-1, in that order
@@ -119,16 +123,16 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
       (s16x4 __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
 }
 
-// Eight bf16 values -> eight E4M3 codes (round to nearest even; values beyond the format's
-// largest finite value, 448, are clamped to it first), element i in byte i.
-__device__ __forceinline__ long bf16x8_to_fp8x8(bf16x8 x) {
+// Eight bf16 values times `mult` -> eight E4M3 codes (round to nearest even; products beyond the
+// format's largest finite value, 448, are clamped to it first), element i in byte i.
+__device__ __forceinline__ long bf16x8_to_fp8x8(bf16x8 x, float mult) {
   union { bf16x8 v; uint32_t w[4]; } u;
   u.v = x;
   int lo = 0, hi = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const float a = __builtin_amdgcn_fmed3f(__uint_as_float(u.w[i] << 16), -448.0f, 448.0f);
-    const float b = __builtin_amdgcn_fmed3f(__uint_as_float(u.w[i] & 0xffff0000u), -448.0f, 448.0f);
+    const float a = __builtin_amdgcn_fmed3f(__uint_as_float(u.w[i] << 16) * mult, -448.0f, 448.0f);
+    const float b = __builtin_amdgcn_fmed3f(__uint_as_float(u.w[i] & 0xffff0000u) * mult, -448.0f, 448.0f);
     // (the half of the word that is written has to be a literal)
     if (i == 0) lo = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, lo, false);
     else if (i == 1) lo = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, lo, true);
@@ -159,29 +163,19 @@ __device__ __forceinline__ long bf16x8_to_fp8x8(bf16x8 x) {
 // takes them from k_new / v_new, and the piece that starts a query tile's key
 // range also copies the tile's token rows into the cache (nothing in this launch
 // reads those cache rows).
-// FP8: keys and values come from a cache of 8-bit codes (OCP E4M3, one byte per element; keys
-// token-major, values in blocks of 64 tokens with the token index fastest, i.e. already in the
-// order the second product contracts them in).  Both products then run on the 8-bit MFMA
-// (v_mfma_f32_32x32x16_fp8_fp8): the query fragments are rounded to E4M3 once per piece, the
-// probabilities once per unit, accumulation stays fp32.  The tensors' scales are folded into
-// the score scale (keys) and into the final normalisation (values) by the launcher.
-template <int D, bool APPEND, bool FP8 = false>
+template <int D, bool APPEND>
 __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
-  static_assert(!(APPEND && FP8), "the fused append reads bf16 rows; the 8-bit cache is filled by its own append kernel");
   constexpr int NT = 512;            // threads
-  constexpr int EB = FP8 ? 1 : 2;    // bytes per K/V element
-  constexpr int NG = D * EB / 16;    // 16-byte granules per K row
+  constexpr int NG = D / 8;          // 16-byte granules per K/V row
   constexpr int KK = D / 16;         // k-steps of S^T = K Q^T
   constexpr int DB = D / 32;         // 32-row blocks of O^T
   constexpr int BN = kKeyTile;
-  constexpr int ROWB = D * EB;       // bytes per K row (and per bf16 V row) in LDS
-  constexpr int TILE_BYTES = BN * ROWB;   // (an 8-bit V tile is D rows of BN bytes: the same size)
+  constexpr int ROWB = D * 2;        // bytes per K/V row in LDS
+  constexpr int TILE_BYTES = BN * ROWB;
   constexpr int VSWZ_MASK = NG / 4 - 1;
   constexpr int NSTAGE = 4;
   constexpr int RPI = 1024 / ROWB;     // tile rows one wave-wide 16-byte load covers
   constexpr int IPW = BN / RPI / 8;    // such loads per wave, per tile, for K and again for V
-  constexpr int NCH = D / 32;          // 1 KiB chunks of a wave's staging area (see below): 32 half rows of D bytes
-  typedef std::conditional_t<FP8, long, bf16x8> frag_t;   // an MFMA operand: 8 elements per lane
   constexpr int KDEPTH = KK / 2;     // K fragments kept in flight (half a unit ahead: four MFMA steps cover the
                                      // LDS latency several times over, and a whole unit costs 16 more registers)
   constexpr int VDEPTH = DB;         // V^T fragments kept in flight
@@ -192,9 +186,6 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // instructions take 16-bit offsets)
   __shared__ __attribute__((aligned(1024))) unsigned char sk[NSTAGE][TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sv[NSTAGE][TILE_BYTES];
-  // FP8: a wave's share of a ring stage is 2 KiB, too small to turn a 32 x D bf16 block around
-  // in; the staging areas get LDS of their own (4 KiB per wave)
-  __shared__ __attribute__((aligned(1024))) unsigned char sq8[FP8 ? 8 * NCH * 1024 : 1024];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -236,32 +227,22 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   };
 
   // ---- this lane's query column (row of the packed (token, head) tile) --------------
-  frag_t qf[KK];
+  bf16x8 qf[KK];
 
   // ---- cooperative K/V tile loads ------------------------------------------------
   // Tiles travel global -> LDS directly (global_load_lds_dwordx4): a wave-wide
   // load drops 64 x 16 bytes at consecutive LDS addresses, i.e. RPI whole rows;
   // the LDS swizzle is applied by choosing which 16-byte granule of the row each
   // lane fetches.  Wave w moves rows (w + 8i) * RPI .. of the tile.
-  // FP8: key rows are D bytes, swizzled by (row / 2) % NG (sixteen consecutive rows then cover
-  // all sixteen 16-byte bank groups); a value tile is one contiguous block of D rows of 64 bytes
-  // (row = element d, byte = key), 16 rows per wave-wide load, a row's four granules swizzled
-  // by (d / 4) % 4.
   const int row_stride = Hkv * D;  // elements between consecutive tokens
   const int lrow = lane / NG;
   const int pg = lane % NG;
-  auto kswz = [&](int r) __attribute__((always_inline)) -> int { return FP8 ? ((r >> 1) % NG) : (r % NG); };
   uint32_t goffk[IPW], goffv[IPW];   // byte offsets of this lane's granules in a full tile
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
     const int r = (wave + 8 * i) * RPI + lrow;
-    goffk[i] = (uint32_t)(r * row_stride * EB + ((pg ^ kswz(r)) * 16));
-    if (FP8) {
-      const int dr = wave * 16 + lane / 4;   // the wave's 16 rows of the block
-      goffv[i] = (uint32_t)(dr * 64 + (((lane % 4) ^ ((dr >> 2) & 3)) * 16));
-    } else {
-      goffv[i] = (uint32_t)(r * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
-    }
+    goffk[i] = (uint32_t)(r * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
+    goffv[i] = (uint32_t)(r * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
   }
   const uint32_t wave_rows = (uint32_t)__builtin_amdgcn_readfirstlane(wave) * 1024u;
 
@@ -272,9 +253,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // therefore travel as whole row pieces (16 bytes per lane, consecutive lanes on
   // consecutive addresses) and are turned around in LDS, half of D at a time.  The
   // staging area is the part of a ring stage that this very wave fills with its
-  // next tile request (NCH chunks of 1 KiB), used at a time when the stage's last
+  // next tile request (2*IPW chunks of 1 KiB), used at a time when the stage's last
   // readers have passed a barrier: no other wave is involved, no barrier needed.
-  // (FP8: a wave's share of a stage is half as large, and the area is LDS of its own.)
   constexpr int RB = D;             // bytes of a row per round (half a row)
   constexpr int NS = RB / 16;       // 16-byte slots of a row per round
   constexpr int RPC = 1024 / RB;    // rows per 1 KiB chunk
@@ -295,13 +275,11 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   // column side: the row of lane ln, (ln & 31), lies in chunk (ln & 31) / RPC; cx_of = its swizzle
   auto cx_of = [&](int ln) __attribute__((always_inline)) -> uint32_t { return (uint32_t)(ln & (NS - 1)) * 16u; };
   auto area_of = [&](int stage, int k) __attribute__((always_inline)) -> uint32_t {   // chunk k of the area in `stage`
-    if (FP8) return lds_addr_of(&sq8[0]) + wave_rows * NCH + (uint32_t)(k * 1024);
     return ((k / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
            (uint32_t)((k % IPW) * 8192);
   };
   auto carea_of = [&](int stage, int ln) __attribute__((always_inline)) -> uint32_t {   // the row of lane ln in its chunk
     const int row = ln & 31;
-    if (FP8) return lds_addr_of(&sq8[0]) + wave_rows * NCH + (uint32_t)((row / RPC) * 1024 + (row % RPC) * RB);
     return (((row / RPC) / IPW) ? lds_addr_of(&sv[0][0]) : lds_addr_of(&sk[0][0])) + (uint32_t)stage * TILE_BYTES + wave_rows +
            (uint32_t)(((row / RPC) % IPW) * 8192 + (row % RPC) * RB);
   };
@@ -314,11 +292,11 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     *tk = t;
     *hk = R - t * G;
   };
-  u32x4 qraw[2][NCH];   // Q row pieces on their way: [half of D][chunk]
+  u32x4 qraw[2][2 * IPW];   // Q row pieces on their way: [half of D][chunk]
   auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
     const int ln = lane_now();
 #pragma unroll
-    for (int k = 0; k < NCH; ++k) {
+    for (int k = 0; k < 2 * IPW; ++k) {
       int hk, tk;
       row_of(ln, k, &hk, &tk);
       // rows beyond the tile repeat a valid row; their columns are never stored
@@ -335,14 +313,12 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
-      for (int k = 0; k < NCH; ++k)
+      for (int k = 0; k < 2 * IPW; ++k)
         *(__attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(area_of(stage, k) + roff) = qraw[h][k];
 #pragma unroll
-      for (int kl = 0; kl < KK / 2; ++kl) {
-        const bf16x8 f = *(const __attribute__((address_space(3))) bf16x8*)(lds_ptr)(uintptr_t)(cbase + ((uint32_t)(kl * 32) ^ cxh));
-        if constexpr (FP8) qf[h * (KK / 2) + kl] = bf16x8_to_fp8x8(f);
-        else qf[h * (KK / 2) + kl] = f;
-      }
+      for (int kl = 0; kl < KK / 2; ++kl)
+        qf[h * (KK / 2) + kl] = *(const __attribute__((address_space(3))) bf16x8*)(lds_ptr)(uintptr_t)(
+            cbase + ((uint32_t)(kl * 32) ^ cxh));
     }
   };
   // The request cursor walks the workgroup's tile stream (all tiles of piece
@@ -352,16 +328,13 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   int c_cached = 0;             // APPEND: how many of them (counted from the next tile on) are in the cache
   // first row of the next tile, this kv-head, as a byte address in k, and (APPEND) where
   // that row would be in k_new; the v addresses are a fixed distance away
-  // (FP8: the value tiles are blocks of their own array, c_v8 = the next one)
-  uintptr_t c_k = 0, c_kn = 0, c_v8 = 0;
+  uintptr_t c_k = 0, c_kn = 0;
   const uintptr_t k_to_v = (uintptr_t)P.v - (uintptr_t)P.k;
   const uintptr_t kn_to_vn = APPEND ? (uintptr_t)P.v_new - (uintptr_t)P.k_new : 0;
-  const uintptr_t tile_step = (uintptr_t)BN * row_stride * EB;
-  const uintptr_t v8_step = (uintptr_t)row_stride * BN;   // one 64-token block of all kv-heads
+  const uintptr_t tile_step = (uintptr_t)BN * row_stride * 2u;
   auto cursor_open = [&]() __attribute__((always_inline)) {
     const AttnItem a = piece(c_piece);
-    c_k = (uintptr_t)P.k + (uintptr_t)((((int64_t)a.kv_row0 + a.k_begin) * Hkv + kvh) * D) * EB;
-    if (FP8) c_v8 = (uintptr_t)P.v + (uintptr_t)(((((int64_t)a.kv_row0 + a.k_begin) / BN) * Hkv + kvh) * D) * BN;
+    c_k = (uintptr_t)(P.k + (((int64_t)a.kv_row0 + a.k_begin) * Hkv + kvh) * D);
     c_left = a.k_end - a.k_begin;
     if (APPEND) {
       const int j0 = tile_of(a) * TM;          // the tile's first token within its chunk
@@ -400,23 +373,21 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     } else {
       const bool all_new = APPEND && c_cached <= 0;
       const uintptr_t bk = all_new ? c_kn : c_k;
-      const uintptr_t bv = FP8 ? c_v8 : bk + (all_new ? kn_to_vn : k_to_v);
+      const uintptr_t bv = bk + (all_new ? kn_to_vn : k_to_v);
 #pragma unroll
       for (int i = 0; i < IPW; ++i) {
         uint32_t ok = goffk[i], ov = goffv[i];
         if (last < BN - 1) {  // ragged last tile: rows past the range repeat the last key
           const int r = (wave + 8 * i) * RPI + lrow;
           const int rc = min(r, last);
-          ok = (uint32_t)(rc * row_stride * EB + ((pg ^ kswz(r)) * 16));
-          // (FP8: a value block is read whole; what lies beyond the last token in it is zero bytes)
-          if (!FP8) ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
+          ok = (uint32_t)(rc * row_stride + ((pg ^ (r % NG)) * 8)) * 2u;
+          ov = (uint32_t)(rc * row_stride + ((pg ^ ((r & VSWZ_MASK) << 2)) * 8)) * 2u;
         }
         async_copy16((const void*)bk, ok, lds_addr_of(&sk[stage][0]) + wave_rows_now + i * 8192u);
         async_copy16((const void*)bv, ov, lds_addr_of(&sv[stage][0]) + wave_rows_now + i * 8192u);
       }
     }
     c_k += tile_step;
-    if (FP8) c_v8 += v8_step;
     if (APPEND) {
       c_kn += tile_step;
       c_cached -= BN;
@@ -445,24 +416,12 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   lds_cptr kptr[KK];   // K fragment of k-step kk, key block 0 (block 1 is +32 rows)
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    uint32_t a = FP8 ? lds_addr_of(&sk[0][0]) + (uint32_t)(l32 * ROWB + ((kk ^ ((l32 >> 1) % NG)) * 16) + hi * 8)
-                     : lds_addr_of(&sk[0][0]) + (uint32_t)(l32 * ROWB + (((kk * 2 + hi) ^ (l32 % NG)) * 16));
+    uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)(l32 * ROWB + (((kk * 2 + hi) ^ (l32 % NG)) * 16));
     asm volatile("" : "+v"(a));
     kptr[kk] = (lds_cptr)(uintptr_t)a;
   }
-  // bf16: V^T fragment of d-block db, keys 4*hi.. of a 16-key group (transposing reads of token-major rows).
-  // FP8: the tile already is V^T (row = element, 64 key bytes); vptr[g] = row l32 of d-block 0, the 16-byte
-  // granule of 16-key group g of the tile, keys 4*hi.. of it; the d-block is an immediate offset.
-  lds_cptr vptr[DB];
-  static_assert(!FP8 || DB == 4, "one pointer per 16-key group of the tile");
-  if constexpr (FP8) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint32_t a = lds_addr_of(&sv[0][0]) + (uint32_t)(l32 * BN + ((g ^ ((l32 >> 2) & 3)) * 16) + 4 * hi);
-      asm volatile("" : "+v"(a));
-      vptr[g] = (lds_cptr)(uintptr_t)a;
-    }
-  } else {
+  lds_cptr vptr[DB];   // V^T fragment of d-block db, keys 4*hi.. of a 16-key group
+  {
     const int j = lane & 15;
     const int half16 = (lane >> 4) & 1;
     const int vrow = 4 * hi + (j >> 2);
@@ -476,44 +435,24 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
   }
   // K fragment (A operand of S^T = K Q^T): keys kb*32 + l32, elements kk*16 + 8*hi..;
   // `off` = stage * TILE_BYTES (an immediate in the main loop)
-  auto ldk = [&](int off, int kb, int kk) __attribute__((always_inline)) -> frag_t {
-    return *(const __attribute__((address_space(3))) frag_t*)(kptr[kk] + off + kb * 32 * ROWB);
+  auto ldk = [&](int off, int kb, int kk) __attribute__((always_inline)) -> bf16x8 {
+    return *(const __attribute__((address_space(3))) bf16x8*)(kptr[kk] + off + kb * 32 * ROWB);
   };
   // V^T fragment (A operand of O^T += V^T P^T) of step j = (16-key group, d-block)
   // of the 32-key unit (stage, kb)
-  auto ldv = [&](int off, int kb, int j) __attribute__((always_inline)) -> frag_t {
-    if constexpr (FP8) {
-      // the lane's eight keys of the group are 4*hi.. and 8 + 4*hi.. (the order the probabilities
-      // sit in the accumulator registers): two 4-byte pieces, 8 bytes apart
-      lds_cptr vp = vptr[2 * kb + j / DB] + off + (j % DB) * 32 * BN;
-      i32x2 w;
-      w[0] = *(const __attribute__((address_space(3))) int*)(vp);
-      w[1] = *(const __attribute__((address_space(3))) int*)(vp + 8);
-      return __builtin_bit_cast(long, w);
-    } else {
-      lds_cptr vp = vptr[j % DB] + off + (2 * kb + j / DB) * 16 * ROWB;
-      union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
-      cat.h.a = lds_read_tr16_l(vp);
-      cat.h.b = lds_read_tr16_l(vp + 8 * ROWB);
-      return cat.v;
-    }
-  };
-  auto mma = [&](const frag_t& a, const frag_t& b, const f32x16& acc) __attribute__((always_inline)) -> f32x16 {
-    if constexpr (FP8) return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, acc, 0, 0, 0);
-    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  auto ldv = [&](int off, int kb, int j) __attribute__((always_inline)) -> bf16x8 {
+    lds_cptr vp = vptr[j % DB] + off + (2 * kb + j / DB) * 16 * ROWB;
+    union { struct { s16x4 a, b; } h; bf16x8 v; } cat;
+    cat.h.a = lds_read_tr16_l(vp);
+    cat.h.b = lds_read_tr16_l(vp + 8 * ROWB);
+    return cat.v;
   };
 
   // A column's reference value m_run (the "running max" of the online softmax) is
   // only moved when the partial row sum of a 32-key unit exceeds 2^24: the weights
   // stay far inside the fp32 / bf16 range, relative precision does not depend on
   // the reference, and the maximum is not needed on the common path.
-  // FP8: the weights are rounded to E4M3, whose largest finite value is 448, so the limit is
-  // 448 (no weight of a unit that is kept exceeds its row sum), and the weights are formed
-  // against the reference minus kBias (in the exponent): a key at the reference weighs 2^kBias,
-  // sixteen of them stay below the limit, and weights keep full precision down to 2^-(6+kBias)
-  // of the reference.  Sum and numerator carry the same factor, which cancels.
-  constexpr float kRowSumLimit = FP8 ? 448.0f : 16777216.0f;
-  constexpr float kBias = FP8 ? 4.0f : 0.0f;
+  constexpr float kRowSumLimit = 16777216.0f;
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
   // ------------------------------------------------------------------------------
@@ -531,14 +470,9 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   f32x16 o[DB];
   f32x16 s[2];                                   // s[u & 1] = S^T of unit u
-  frag_t ka[KDEPTH];                             // K fragments in flight: step j of a unit sits in ka[j % KDEPTH]
-  frag_t vf[VDEPTH];                             // V^T fragments in flight, likewise
+  bf16x8 ka[KDEPTH];                             // K fragments in flight: step j of a unit sits in ka[j % KDEPTH]
+  bf16x8 vf[VDEPTH];                             // V^T fragments in flight, likewise
   union { bf16x2 h[8]; bf16x8 v[2]; } pf[2];     // pf[u & 1] = probabilities of unit u, B-operand layout
-  i32x2 pf8[2][2];                               // FP8: the same as bytes, pair pr in half pr % 2 of word pr / 2
-  auto pfrag = [&](int u, int g) __attribute__((always_inline)) -> frag_t {
-    if constexpr (FP8) return __builtin_bit_cast(long, pf8[u][g]);
-    else return pf[u].v[g];
-  };
   float m_run, l_run, mc, rs0 = 0.f, rs1 = 0.f;
 
   // state of the piece being computed
@@ -557,22 +491,6 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     asm volatile("" : "+v"(x0), "+v"(x1));
     const float p0 = fast_exp2(fmaf(x0, c, -mc));
     const float p1 = fast_exp2(fmaf(x1, c, -mc));
-    if constexpr (FP8) {
-      // (the sum takes the weights before rounding: rounding to nearest is unbiased, and turning the
-      // codes back into numbers would cost more than the two additions)
-      int w = pf8[cur][pr / 4][(pr / 2) % 2];
-      if (pr & 1) {
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, w, true);
-        rs1 += p0 + p1;
-        asm volatile("" : "+v"(w), "+v"(rs1));
-      } else {
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, w, false);
-        rs0 += p0 + p1;
-        asm volatile("" : "+v"(w), "+v"(rs0));
-      }
-      pf8[cur][pr / 4][(pr / 2) % 2] = w;
-      return;
-    }
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
@@ -616,10 +534,10 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
 #pragma unroll
     for (int i = 0; i < QS; ++i) {
-      s[nxt] = mma(ka[i % KDEPTH], qf[i], s[nxt]);
+      s[nxt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[nxt], 0, 0, 0);
       ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk(st_n * TILE_BYTES, kb_n, i + KDEPTH)
                                          : ldk(st_nn * TILE_BYTES, kb_nn, i + KDEPTH - QS);
-      o[i % DB] = mma(vf[i % VDEPTH], pfrag(nxt, i / DB), o[i % DB]);
+      o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pf[nxt].v[i / DB], o[i % DB], 0, 0, 0);
       vf[i % VDEPTH] = (i + VDEPTH < PS) ? ldv(st_p * TILE_BYTES, kb_p, i + VDEPTH)
                                          : ldv(st_c * TILE_BYTES, kb_c, i + VDEPTH - PS);
 #pragma unroll
@@ -628,7 +546,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       // other MFMA, the two transposed V reads, the rest of the vector work
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x402, (FP8 ? 4 : 3) * PPS, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x402, 3 * PPS, 0);
@@ -637,8 +555,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     float rs = rs0 + rs1;
     // pin the vector work above to this block: without a use here the compiler
     // sinks it below the branch that follows, away from the MFMAs it should hide under
-    if constexpr (FP8) asm volatile("" : "+v"(pf8[cur][0]), "+v"(pf8[cur][1]), "+v"(rs));
-    else asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(rs));
+    asm volatile("" : "+v"(pf[cur].v[0]), "+v"(pf[cur].v[1]), "+v"(rs));
     __builtin_amdgcn_sched_barrier(0);
     if (u == 0) {
       // the O^T MFMAs of a piece's first body belong to no unit (zero probabilities
@@ -663,7 +580,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = fast_exp2((m_run - m_new) * c);
       m_run = m_new;
-      mc = m_run * c - kBias;
+      mc = m_run * c;
       l_run *= alpha;
       rs0 = 0.f;
       rs1 = 0.f;
@@ -729,7 +646,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     {
       float c_now = c;
       asm volatile("" : "+s"(c_now));
-      mc = m_run * c_now - kBias;
+      mc = m_run * c_now;
     }
     // the accumulators start undefined (they are cleared after the first body, see
     // unit_body); saying so ends their live range at the previous piece's epilogue
@@ -753,19 +670,15 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       // ring position of unit 0 is 2*ph: s[] and pf[] are indexed by its parity, 0
 #pragma unroll
       for (int i = 0; i < QS; ++i) {
-        s[0] = mma(ka[i % KDEPTH], qf[i], s[0]);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i % KDEPTH], qf[i], s[0], 0, 0, 0);
         ka[i % KDEPTH] = (i + KDEPTH < QS) ? ldk(off0, 0, i + KDEPTH) : ldk(off0, 1, i + KDEPTH - QS);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int j = 0; j < VDEPTH; ++j) vf[j] = ldv(offm, 1, j);
-      if constexpr (FP8) {
-        pf8[1][0] = pf8[1][1] = i32x2{0, 0};
-      } else {
-        const bf16x2 z2 = {(__bf16)0.0f, (__bf16)0.0f};
+      const bf16x2 z2 = {(__bf16)0.0f, (__bf16)0.0f};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pf[1].h[j] = z2;
-      }
+      for (int j = 0; j < 8; ++j) pf[1].h[j] = z2;
     }
 
     // tiles of the piece, the loop unrolled over the four ring stages
@@ -796,7 +709,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     } else {
       // (defined on every path, so that the values are not kept alive across the key loop)
 #pragma unroll
-      for (int k = 0; k < NCH; ++k) qraw[0][k] = qraw[1][k] = u32x4{0u, 0u, 0u, 0u};
+      for (int k = 0; k < 2 * IPW; ++k) qraw[0][k] = qraw[1][k] = u32x4{0u, 0u, 0u, 0u};
     }
     const int st_area = (ph + nt + 2) & 3;   // the stage the next tile request goes to
 
@@ -845,13 +758,13 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       // the fragments preloaded by the last body belong to this unit already; its
       // probabilities are pf[ul & 1] (picked as values: an array indexed at run time
       // would be put into scratch memory)
-      frag_t e0 = pfrag(0, 0), e1 = pfrag(0, 1), d0 = pfrag(1, 0), d1 = pfrag(1, 1);
+      bf16x8 e0 = pf[0].v[0], e1 = pf[0].v[1], d0 = pf[1].v[0], d1 = pf[1].v[1];
       asm volatile("" : "+v"(e0), "+v"(e1), "+v"(d0), "+v"(d1));
       const bool odd = (ul & 1) != 0;
-      const frag_t pl[2] = {odd ? d0 : e0, odd ? d1 : e1};
+      const bf16x8 pl[2] = {odd ? d0 : e0, odd ? d1 : e1};
 #pragma unroll
       for (int i = 0; i < PS; ++i) {
-        o[i % DB] = mma(vf[i % VDEPTH], pl[i / DB], o[i % DB]);
+        o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VDEPTH], pl[i / DB], o[i % DB], 0, 0, 0);
         if (i + VDEPTH < PS) vf[i % VDEPTH] = ldv(off, kb, i + VDEPTH);
       }
     }
@@ -863,13 +776,13 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
       // rows further down) are stored with the non-temporal hint: nothing in this launch reads
       // them again, and lines that do not linger dirty in the level-2 cache need no write-back
       // when the kernel ends.
-      const float inv = FP8 ? P.out_scale / l_tot : 1.0f / l_tot;
+      const float inv = 1.0f / l_tot;
       const int ln = lane_now();
       const uint32_t roff = roff_of(ln), cx = cx_of(ln);
       const uint32_t wbase = carea_of(st_area, ln) + (uint32_t)(ln >> 5) * 8u;
-      int grow[NCH];                    // head-row (token * Hq + head) of the row in out, -1: not a row of this tile
+      int grow[2 * IPW];                // head-row (token * Hq + head) of the row in out, -1: not a row of this tile
 #pragma unroll
-      for (int k = 0; k < NCH; ++k) {
+      for (int k = 0; k < 2 * IPW; ++k) {
         int hk, tk;
         row_of(ln, k, &hk, &tk);
         grow[k] = tk < tokens_of(done) ? (done.q_row0 + tk) * Hq + kvh * G + hk : -1;
@@ -886,7 +799,7 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
             *(__attribute__((address_space(3))) bf16x4*)(lds_ptr)(uintptr_t)(wbase + ((uint32_t)((dbl * 4 + b) * 16) ^ cx)) = w;
           }
 #pragma unroll
-        for (int k = 0; k < NCH; ++k) {
+        for (int k = 0; k < 2 * IPW; ++k) {
           const u32x4 val = *(const __attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(
               area_of(st_area, k) + roff);
           if (grow[k] >= 0) __builtin_nontemporal_store(val, (u32x4*)(P.out + (int64_t)grow[k] * D + (ln % NS) * 8 + h * (D / 2)));
@@ -935,6 +848,8 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
     ph = (ph + nt) & 3;
   }
 }
+
+#include "attn_fp8_kernel.h"
 
 // Merge the partial (max, sum, unnormalised O) of the pieces of a split tile
 // (at most kMaxSplit pieces):
@@ -1250,6 +1165,17 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   P.TM = ls.TM;
   P.c = ls.c;
   P.out_scale = ls.out_scale;
+  P.q_mult = 1.0f;
+  P.q_scale_byte = 127;
+  if (ls.fp8) {
+    // k with 4 <= c * 2^k < 8: queries of magnitude 2^-8 .. 56 stay inside E4M3's normal range
+    int e = 0;
+    (void)frexpf(ls.c, &e);                  // c = f * 2^e, 0.5 <= f < 1
+    const int k = 3 - e;                     // c * 2^k = 8 f, in [4, 8)
+    if (k < -120 || k > 120) return (int)hipErrorInvalidValue;
+    P.q_mult = ldexpf(ls.c, k);
+    P.q_scale_byte = 127 - k;
+  }
   P.n_queues = n_queues;
   P.g_magic = (65536u + (uint32_t)ls.G - 1u) / (uint32_t)ls.G;
   for (int j = 0; j <= n_queues; ++j) P.first[j] = first[j];
@@ -1260,7 +1186,7 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   if (ls.fp8) {
     // (the 8-bit cache is filled by its own append kernel, and only the head size 128 is built)
     if (append || ls.D != 128) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_fwd_kernel<128, false, true>), grid, dim3(512), 0, st, P);
+    hipLaunchKernelGGL(attn_fwd_fp8_kernel, grid, dim3(512), 0, st, P);
   } else if (ls.D == 128) {
     if (append) hipLaunchKernelGGL((attn_fwd_kernel<128, true>), grid, dim3(512), 0, st, P);
     else hipLaunchKernelGGL((attn_fwd_kernel<128, false>), grid, dim3(512), 0, st, P);
@@ -1284,7 +1210,7 @@ int launch_combine(const LayerShape& ls, void* out, const float* part_o, const f
     P.Hkv = ls.Hkv;
     P.G = ls.G;
     P.TM = ls.TM;
-    P.c = ls.c;
+    P.c = ls.fp8 ? 1.0f : ls.c;   // (the 8-bit kernel stores its references in log2 units)
     P.out_scale = ls.out_scale;
     const int n = n_items - base < kMaxCombineItems ? n_items - base : kMaxCombineItems;
     P.n_items = n;
