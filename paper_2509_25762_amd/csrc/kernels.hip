@@ -483,12 +483,12 @@ __global__ __launch_bounds__(512) void attn_fwd_kernel(const AttnParams P) {
 
   // probabilities 2p, 2p+1 of the unit in s[cur]: exp2, round to bf16, add to the
   // row sum (the sum uses the rounded values, like the numerator does)
-  // The two empty asm statements pin the work to its place in the instruction
-  // stream: the inputs only "exist" after the first, the results are "used" by
-  // the second, and such statements keep their order.
+  // The empty asm statement pins the work to its place in the instruction stream: the
+  // results are "used" by it, and such statements keep their order.  (The inputs are read
+  // from the score registers as they are: a statement that "defines" them as well costs a
+  // register copy per score, because the scores have to survive for a possible redo.)
   auto exp_pair = [&](int cur, int pr) __attribute__((always_inline)) {
-    float x0 = s[cur][2 * pr], x1 = s[cur][2 * pr + 1];
-    asm volatile("" : "+v"(x0), "+v"(x1));
+    const float x0 = s[cur][2 * pr], x1 = s[cur][2 * pr + 1];
     const float p0 = fast_exp2(fmaf(x0, c, -mc));
     const float p1 = fast_exp2(fmaf(x1, c, -mc));
     bf16x2 pk;
