@@ -263,3 +263,69 @@ def test_tiny_config_through_the_8_bit_cache_is_refused_for_head_size_64(gpu):
     torch.cuda.synchronize()
     cache, _ = oracle_run_codes_only(ep, chunks, se.slot_begin, 1.0, 1.0)
     check_codes(se, cache)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_small_chunk_workload_through_the_8_bit_cache(gpu):
+    """Config 3 (256 sequences, C = 64) at full size, in the launch configuration bench.py --fp8-cache
+    times.  For every eighth sequence plus the shortest and the longest (the oracle's conversion takes
+    0.15 ms per token): the codes against the oracle's, every byte of the slab, and the attention on rows
+    the oracle computes one by one over the values its codes stand for - every row of the shortest
+    sequence, the chunk-boundary rows of the others (one q-head each), plus random rows of the longest.
+    For all sequences: lengths, and all outputs finite."""
+    binding, episode, torch = gpu
+    from oracle import causal_attention
+    from oracle.fp8_cache import dequantize, quantize
+    cfg = CONFIGS[3]
+    ep = build_episode(cfg, threads=16)
+    P, R = ep.prompt_len, ep.resp_len
+    B, Hq, G = cfg.batch, cfg.num_q_heads, cfg.group
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(P, R, cfg.chunk)
+    print(f"config 3 through the 8-bit cache: {int(ep.tok_begin[-1])} tokens, {len(chunks) - 1} response passes", flush=True)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    out = se.scatter_outputs().cpu().numpy().view(np.uint16)
+    assert np.isfinite(bf16_bits_to_f64(out)).all()
+    gk = se.cache_k.cpu().numpy()
+    gv = se.cache_v.cpu().numpy()
+    n_tok = P.astype(np.int64) + R
+    rng = np.random.default_rng(cfg.seed + 8)
+    errs = []
+    shortest, longest = int(np.argmin(n_tok)), int(np.argmax(n_tok))
+    assert np.array_equal(se.cache.kv_len, n_tok)
+    for i in sorted(set(range(0, B, 8)) | {shortest, longest}):
+        lo, n = int(ep.tok_begin[i]), int(n_tok[i])
+        b, e = int(se.slot_begin[i]), int(se.slot_begin[i + 1])
+        # ---- codes and layout of this sequence's slab, every byte
+        kc = quantize(ep.k[lo:lo + n], ks)
+        vc = quantize(ep.v[lo:lo + n], vs)
+        assert np.array_equal(gk[b:b + n], kc), f"key codes of sequence {i}"
+        assert (gk[b + n:e] == 0xFF).all(), f"key slots behind sequence {i} touched"
+        want_v = np.full((e - b, cfg.num_kv_heads, cfg.head_dim), 0xFF, dtype=np.uint8)
+        want_v[:n] = vc
+        want_v[n:(n + 63) // 64 * 64] = 0                                   # the rest of the last block touched
+        got_v = gv[b // 64:e // 64].transpose(0, 3, 1, 2).reshape(e - b, cfg.num_kv_heads, cfg.head_dim)
+        assert np.array_equal(got_v, want_v), f"value codes of sequence {i}"
+        # ---- sampled rows
+        bounds = {0, int(P[i]) - 1, n - 1}
+        for t in range(num_steps(R, cfg.chunk)):
+            kvb, ql, _ = chunk_schedule(P[i:i + 1], R[i:i + 1], cfg.chunk, t)
+            if ql[0] > 0:
+                bounds |= {int(kvb[0]), int(kvb[0] + ql[0] - 1)}
+        pos = np.array(sorted(bounds), dtype=np.int64)
+        heads = [i % Hq]
+        if i == shortest:
+            pos, heads = np.arange(n), [0, Hq - 1]
+        elif i == longest:
+            pos = np.unique(np.concatenate([pos, rng.integers(0, n, size=256)]))
+            heads = [0, Hq - 1]
+        for h in heads:
+            g = h // G
+            kd = dequantize(kc[:, g:g + 1], ks)
+            vd = dequantize(vc[:, g:g + 1], vs)
+            q = bf16_bits_to_f64(ep.q[lo + pos, h])[:, None, :]
+            ref = causal_attention(q, kd, vd, pos, cfg.softmax_scale)[:, 0]
+            errs.append(np.abs(bf16_bits_to_f64(out[lo + pos, h]) - ref).ravel())
+    err = np.concatenate(errs)
+    print(f"config 3 through the 8-bit cache: {err.size} sampled elements, max abs {err.max():.3e} mean abs {err.mean():.3e}", flush=True)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
