@@ -260,7 +260,6 @@ size_t oppo_static_scratch_bytes(void);
  *            k[slot][Hkv][D]; values in blocks of 64 tokens with the token index fastest,
  *            v[slot / 64][Hkv][D][slot % 64] (the order in which the second product of
  *            attention contracts them).  Every slot_begin[i] is a multiple of 64.
- * Only head_dim 128 is built for attention over this cache; the append also takes 64.
  */
 typedef struct {
   void* k;                   /* device bytes [total_slots][Hkv][D]                      */
@@ -298,8 +297,8 @@ int oppo_kv_append_fp8(const oppo_attn_desc* desc, oppo_kv_cache_fp8* cache,
  * exact attention over the stored values by the rounding of queries and weights - a few
  * percent of a value's magnitude per element for short rows, less for long ones - on top
  * of the error of storing K and V in 8 bits.  Workspace rules as oppo_chunk_prefill_attn.
- * Errors: as oppo_chunk_prefill_attn; UNSUPPORTED for head_dim != 128; INVALID for bad
- * scales or slab starts that are not multiples of 64.
+ * Errors: as oppo_chunk_prefill_attn; INVALID for bad scales or slab starts that are not
+ * multiples of 64.
  */
 int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_fp8* cache,
                                 const int32_t* cu_q /* host [batch+1] */,

@@ -811,7 +811,6 @@ int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_
   oppo_kv_cache view;
   rc = check_cache_fp8(cache, &view);
   if (rc) return rc;
-  if (ls.D != 128) return fail(OPPO_ERR_UNSUPPORTED, "attention over the 8-bit cache is built for head_dim 128 only");
   const int32_t B = view.batch;
   rc = check_cu(cu_q, B, "cu_q");
   if (rc) return rc;

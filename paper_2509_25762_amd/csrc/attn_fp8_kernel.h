@@ -44,8 +44,11 @@
 // additions).  A column's first reference is the maximum of the first unit in which it sees a
 // key; until then it is the arbitrary 0 and the column has accumulated nothing.
 // The values' scale is folded into the final normalisation.
+// Head size 64: the contraction of S^T is one MFMA deep, O^T has two 32-row blocks; a tile of
+// either array is 4 KiB, so waves 0-3 move the keys and waves 4-7 the values.
+template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
-  constexpr int D = 128;
+  static_assert(D == 128 || D == 64, "head sizes 64 and 128");
   constexpr int NT = 512;
   constexpr int BN = kKeyTile;
   constexpr int ROWB = D;                  // bytes per key row
@@ -53,7 +56,11 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
   constexpr int NSTAGE = 4;
   constexpr int NCH = D / 32;              // 1 KiB chunks of a wave's staging area
   constexpr int DB = D / 32;               // 32-row blocks of O^T
-  static_assert(BN == 64 && TILE_BYTES == 8192, "one wave-wide 16-byte load per wave, tile and array");
+  constexpr int KS = D / 64;               // MFMAs of S^T per unit = O^T MFMAs per unit body
+  constexpr int NGK = ROWB / 16;           // 16-byte granules per key row
+  constexpr int UM = D / 32 - 1;           // a key row's 32-byte units are swizzled by (row >> KSH) & UM
+  constexpr int KSH = D == 128 ? 1 : 2;
+  static_assert(BN == 64, "64-key tiles");
 
   __shared__ __attribute__((aligned(1024))) unsigned char sk[NSTAGE][TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sv[NSTAGE][TILE_BYTES];
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
     for (int i = tid; i < n16; i += NT) ((u32x4*)spiece)[i] = src[i];
     // The first piece's first tile multiplies zero weights with "the tile before it", whatever ring
     // stage 3 holds: make that zero bytes (valid codes; afterwards the ring only ever holds codes).
-    ((u32x4*)&sv[NSTAGE - 1][0])[tid] = u32x4{0u, 0u, 0u, 0u};
+    if (tid < TILE_BYTES / 16) ((u32x4*)&sv[NSTAGE - 1][0])[tid] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
   }
   auto piece = [&](int p) __attribute__((always_inline)) -> AttnItem {
@@ -101,17 +108,22 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
   };
 
   // ---- cooperative K/V tile loads (global -> LDS directly, 16 bytes per lane) ----------------
-  // K: a wave-wide load covers 8 key rows (8 granules of 16 bytes each); wave w moves rows 8w ...
-  // A row's four 32-byte units (the piece of a row one lane reads as an MFMA operand) are
-  // swizzled by (row / 2) % 4.  V: a tile is one contiguous block of D rows of 64 key bytes;
-  // wave w moves rows 16w ..; a row's two 32-byte units are swizzled by (row / 4) % 2.
+  // K: a wave-wide load covers 1 KiB of key rows (8 rows of D = 128, 16 of D = 64).  A row's
+  // 32-byte units (the piece of a row one lane reads as an MFMA operand) are swizzled by
+  // (row / 2) % 4 resp. (row / 4) % 2.  V: a tile is one contiguous block of D rows of 64 key
+  // bytes, 16 rows per wave-wide load; a row's two 32-byte units are swizzled by (row / 4) % 2.
+  // D = 128: every wave moves 1 KiB of each; D = 64: waves 0-3 the keys, waves 4-7 the values.
   const int row_stride = Hkv * D;   // bytes between consecutive tokens' keys
-  const int kr = wave * 8 + lane / 8;
-  const int kg = lane % 8;
-  const uint32_t goffk = (uint32_t)(kr * row_stride + ((kg ^ (((kr >> 1) & 3) << 1)) * 16));
-  const int vr = wave * 16 + lane / 4;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const bool moves_k = D == 128 || wave_s < 4, moves_v = D == 128 || wave_s >= 4;
+  const int kwave = wave_s, vwave = D == 128 ? wave_s : (wave_s & 3);
+  const int kr = (kwave & (TILE_BYTES / 1024 - 1)) * (64 / NGK) + lane / NGK;
+  const int kg = lane % NGK;
+  const uint32_t goffk = (uint32_t)(kr * row_stride + ((kg ^ (((kr >> KSH) & UM) << 1)) * 16));
+  const int vr = vwave * 16 + lane / 4;
   const uint32_t goffv = (uint32_t)(vr * BN + (((lane % 4) ^ (((vr >> 2) & 1) << 1)) * 16));
-  const uint32_t wave_rows = (uint32_t)__builtin_amdgcn_readfirstlane(wave) * 1024u;
+  const uint32_t wave_rows = (uint32_t)wave_s * 1024u;
+  const uint32_t kdst = (uint32_t)(kwave & (TILE_BYTES / 1024 - 1)) * 1024u, vdst = (uint32_t)vwave * 1024u;
 
   // ---- the wave's staging area -----------------------------------------------------------------
   // Q and O blocks travel to and from global memory as whole row pieces (16 bytes per lane,
@@ -147,7 +159,7 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
     *tk = t;
     *hk = R - t * G;
   };
-  i32x8 qf[2];            // the lane's query column as E4M3 codes: elements 64 kk + 32 hi .. of it in qf[kk]
+  i32x8 qf[KS];           // the lane's query column as E4M3 codes: elements 64 kk + 32 hi .. of it in qf[kk]
   u32x4 qraw[2][NCH];     // Q row pieces on their way: [half of D][chunk]
   auto q_request = [&](const AttnItem& a) __attribute__((always_inline)) {
     const int ln = lane_now();
@@ -172,14 +184,24 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
 #pragma unroll
       for (int k = 0; k < NCH; ++k)
         *(__attribute__((address_space(3))) u32x4*)(lds_ptr)(uintptr_t)(area_of(k) + roff) = qraw[h][k];
-      // round h holds elements 64 h .. of every row; the lane wants 32 hl .. of them: slots 4 hl + j
+      // round h holds elements (D / 2) h .. of every row.  D = 128: the lane wants 32 hl .. of them (slots
+      // 4 hl + j) for its operand of contraction half h; D = 64: round hl as a whole is the lane's operand
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
+        const int sl = D == 128 ? 4 * hl + j : j;
         const bf16x8 f = *(const __attribute__((address_space(3))) bf16x8*)(lds_ptr)(uintptr_t)(
-            cbase + ((uint32_t)((4 * hl + j) * 16) ^ cx));
+            cbase + ((uint32_t)(sl * 16) ^ cx));
         const long w = bf16x8_to_fp8x8(f, q_mult);
-        qf[h][2 * j] = (int)(uint32_t)((unsigned long)w & 0xffffffffu);
-        qf[h][2 * j + 1] = (int)(uint32_t)((unsigned long)w >> 32);
+        const int w0 = (int)(uint32_t)((unsigned long)w & 0xffffffffu), w1 = (int)(uint32_t)((unsigned long)w >> 32);
+        if constexpr (D == 128) {
+          qf[h][2 * j] = w0;
+          qf[h][2 * j + 1] = w1;
+        } else {
+          if (h == 0 || hl == 1) {   // (round 0 for the lower lanes, overwritten by round 1 for the upper ones)
+            qf[0][2 * j] = w0;
+            qf[0][2 * j + 1] = w1;
+          }
+        }
       }
     }
   };
@@ -202,14 +224,17 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
     const int last = c_left - 1;
     uint32_t wave_rows_now = wave_rows;
     asm volatile("" : "+s"(wave_rows_now));
+    (void)wave_rows_now;
     uint32_t ok = goffk;
     if (last < BN - 1) {  // ragged last tile: rows past the range repeat the last key
       const int rc = min(kr, last);
-      ok = (uint32_t)(rc * row_stride + ((kg ^ (((kr >> 1) & 3) << 1)) * 16));
+      ok = (uint32_t)(rc * row_stride + ((kg ^ (((kr >> KSH) & UM) << 1)) * 16));
     }
+    uint32_t kd = kdst, vd = vdst;
+    asm volatile("" : "+s"(kd), "+s"(vd));
     // (a value block is read whole: what lies beyond the last token in it is later tokens' codes or zeros)
-    async_copy16((const void*)c_k, ok, lds_addr_of(&sk[stage][0]) + wave_rows_now);
-    async_copy16((const void*)c_v, goffv, lds_addr_of(&sv[stage][0]) + wave_rows_now);
+    if (moves_k) async_copy16((const void*)c_k, ok, lds_addr_of(&sk[stage][0]) + kd);
+    if (moves_v) async_copy16((const void*)c_v, goffv, lds_addr_of(&sv[stage][0]) + vd);
     c_k += k_step;
     c_v += v_step;
     c_left -= BN;
@@ -226,12 +251,12 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
 
   // ---- per-lane LDS addresses of the operand fragments ----------------------------------------
   // K: MFMA row l32 = 8a + 4h' + b of unit 0 is the tile's key row 32h' + 4a + b (unit 1: 16 rows further)
-  lds_cptr kptr[2];   // elements 64 kk + 32 hi .. of that row
+  lds_cptr kptr[KS];   // elements 64 kk + 32 hi .. of that row
   {
     const int krow = 32 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)(krow * ROWB + (((2 * kk + hi) ^ ((krow >> 1) & 3)) * 32));
+    for (int kk = 0; kk < KS; ++kk) {
+      uint32_t a = lds_addr_of(&sk[0][0]) + (uint32_t)(krow * ROWB + (((2 * kk + hi) ^ ((krow >> KSH) & UM)) * 32));
       asm volatile("" : "+v"(a));
       kptr[kk] = (lds_cptr)(uintptr_t)a;
     }
@@ -275,8 +300,8 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
   // ------------------------------------------------------------------------------------------
   f32x16 o[DB];
   f32x16 s[2];          // s[u & 1] = S^T of unit u
-  i32x8 ka[2];          // K fragments in flight (the two contraction halves of a unit)
-  i32x8 vf[2];          // V^T fragments in flight
+  i32x8 ka[KS];         // K fragments in flight (the contraction halves of a unit)
+  i32x8 vf[KS];         // V^T fragments in flight
   i32x8 pw[2];          // pw[tile's ring stage & 1] = the tile's weights, B-operand layout (byte j = key 32 hi + j)
   f32x16 negm;          // kBias minus the column's reference (log2 units), in all sixteen registers
   float mref = 0.f;     // the reference
@@ -327,25 +352,26 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
     rs0 = 0.f;
     rs1 = 0.f;
 
+    constexpr int PPSN = 8 / KS;   // pairs of weights per step
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < KS; ++i) {
       s[nxt] = mma_s(ka[i], qf[i], i == 0 ? negm : s[nxt]);
-      ka[i] = ldk(st_nn * TILE_BYTES, ub, i);     // (unit u+1's other fragment is already in ka[1 - i] or consumed next)
-      o[2 * ub + i] = mma(vf[i], pw[tq], o[2 * ub + i]);
-      // the O^T MFMA after this one in program order: d-block 2 + i of the same tile (ub = 0), or
+      ka[i] = ldk(st_nn * TILE_BYTES, ub, i);
+      o[KS * ub + i] = mma(vf[i], pw[tq], o[KS * ub + i]);
+      // the O^T MFMA after this one in program order: d-block KS + i of the same tile (ub = 0), or
       // d-block i of the tile that is current now (ub = 1)
-      vf[i] = ub == 0 ? ldv(st_p * TILE_BYTES, 2 + i) : ldv(st_c * TILE_BYTES, i);
+      vf[i] = ub == 0 ? ldv(st_p * TILE_BYTES, KS + i) : ldv(st_c * TILE_BYTES, i);
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int pr = 4 * i + jj;
+      for (int jj = 0; jj < PPSN; ++jj) {
+        const int pr = PPSN * i + jj;
         pw[tp][4 * ub + pr / 2] = exp_pair(cur, pr, pw[tp][4 * ub + pr / 2], 0.f);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x402, 10, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 5 * PPSN / 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x402, 10, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 5 * PPSN / 2, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
     (void)st_n;
@@ -353,7 +379,8 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
     float rs = rs0 + rs1;
     // pin the work above to this block: without a use here the compiler sinks it - the MFMAs
     // included - below the branch that follows
-    asm volatile("" : "+v"(pw[tp]), "+v"(rs), "+v"(s[nxt]), "+v"(o[2 * ub]), "+v"(o[2 * ub + 1]));
+    if constexpr (KS == 2) asm volatile("" : "+v"(pw[tp]), "+v"(rs), "+v"(s[nxt]), "+v"(o[2 * ub]), "+v"(o[2 * ub + 1]));
+    else asm volatile("" : "+v"(pw[tp]), "+v"(rs), "+v"(s[nxt]), "+v"(o[ub]));
     __builtin_amdgcn_sched_barrier(0);
     // (the O^T MFMAs of a piece's first tile multiply zero weights with a tile of valid codes: nothing)
     const bool over = __any(rs > kRowSumLimit);
@@ -469,15 +496,15 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
       const int off0 = ph * TILE_BYTES;
       const int offm = ((ph + 3) & 3) * TILE_BYTES;   // "the previous tile": any stage
 #pragma unroll
-      for (int i = 0; i < 2; ++i) ka[i] = ldk(off0, 0, i);
+      for (int i = 0; i < KS; ++i) ka[i] = ldk(off0, 0, i);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < KS; ++i) {
         s[0] = mma_s(ka[i], qf[i], i == 0 ? negm : s[0]);
         ka[i] = ldk(off0, 1, i);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i) vf[i] = ldv(offm, i);
+      for (int i = 0; i < KS; ++i) vf[i] = ldv(offm, i);
     }
 
     const int tau1 = ph + nt;
@@ -513,14 +540,14 @@ __global__ __launch_bounds__(512) void attn_fwd_fp8_kernel(const AttnParams P) {
       const int sl = (ph + nt - 1) & 3;
       const int off = sl * TILE_BYTES;
       // its weights are pw[sl & 1] (picked as values: an array indexed at run time would be put
-      // into scratch memory); the fragments of d-blocks 0 and 1 were preloaded by the last body
+      // into scratch memory); the fragments of the first KS d-blocks were preloaded by the last body
       i32x8 e = pw[0], d = pw[1];
       asm volatile("" : "+v"(e), "+v"(d));
       const i32x8 pl = (sl & 1) ? d : e;
 #pragma unroll
       for (int i = 0; i < DB; ++i) {
-        o[i] = mma(vf[i % 2], pl, o[i]);
-        if (i + 2 < DB) vf[i % 2] = ldv(off, i + 2);
+        o[i] = mma(vf[i % KS], pl, o[i]);
+        if (i + KS < DB) vf[i % KS] = ldv(off, i + KS);
       }
     }
 

@@ -1184,9 +1184,10 @@ int launch_attention(const LayerShape& ls, const void* q, void* k, void* v, cons
   const bool append = k_new != nullptr;
   const int pair = timed ? prof_begin(0, st) : -1;
   if (ls.fp8) {
-    // (the 8-bit cache is filled by its own append kernel, and only the head size 128 is built)
-    if (append || ls.D != 128) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(attn_fwd_fp8_kernel, grid, dim3(512), 0, st, P);
+    // (the 8-bit cache is filled by its own append kernel)
+    if (append) return (int)hipErrorInvalidValue;
+    if (ls.D == 128) hipLaunchKernelGGL(attn_fwd_fp8_kernel<128>, grid, dim3(512), 0, st, P);
+    else hipLaunchKernelGGL(attn_fwd_fp8_kernel<64>, grid, dim3(512), 0, st, P);
   } else if (ls.D == 128) {
     if (append) hipLaunchKernelGGL((attn_fwd_kernel<128, true>), grid, dim3(512), 0, st, P);
     else hipLaunchKernelGGL((attn_fwd_kernel<128, false>), grid, dim3(512), 0, st, P);

@@ -26,7 +26,7 @@ int launch_attention(const LayerShape& ls, const void*, void*, void*, const void
     if (n < 1 || n > ls.TM) return 1;
     if (a.k_begin < 0 || a.k_begin % kKeyTile != 0 || a.k_end <= a.k_begin || a.k_end > a.pos0 + n) return 1;
     if (a.part >= 0 && !part_o) return 1;
-    if (ls.fp8 && (ls.D != 128 || a.kv_row0 % kKeyTile != 0)) return 1;
+    if (ls.fp8 && a.kv_row0 % kKeyTile != 0) return 1;
   }
   return 0;
 }

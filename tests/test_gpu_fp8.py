@@ -249,20 +249,32 @@ def test_attention_dominant_keys_and_single_key_rows(gpu):
         assert err[int(ep.tok_begin[i])].max() <= 2.0 ** -8 * np.abs(ref[int(ep.tok_begin[i])]).max() + 1e-6
 
 
-def test_tiny_config_through_the_8_bit_cache_is_refused_for_head_size_64(gpu):
-    binding, episode, torch = gpu
+@pytest.mark.parametrize("C", [7, 32, 100])
+def test_tiny_config_through_the_8_bit_cache(gpu, C):
+    """The tiny workload (head size 64, no grouping: 4 q-heads on 4 kv-heads) streamed through the
+    8-bit cache: codes bit for bit, attention on all rows."""
     ep = build_episode(CONFIGS[1], threads=2)
     assert ep.cfg.head_dim == 64
-    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, 32)[:1]
-    se = episode.StreamedEpisodeFp8(ep, chunks, 1.0, 1.0)
-    s = se.steps[0]
-    binding.oppo_kv_append_fp8(se.desc, se.cache, s.cu_q, s.k, s.v)     # the append takes head size 64
-    with pytest.raises(binding.OppoError) as e:
-        binding.oppo_chunk_prefill_attn_fp8(se.desc, se.cache, s.cu_q, s.q, s.out, se.workspace)
-    assert e.value.code == binding.OPPO_ERR_UNSUPPORTED
-    torch.cuda.synchronize()
-    cache, _ = oracle_run_codes_only(ep, chunks, se.slot_begin, 1.0, 1.0)
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, C)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    cache, ref = oracle_run(ep, chunks, se.slot_begin, ks, vs)
     check_codes(se, cache)
+    check_outputs(se, ref, f"fp8 tiny C={C}")
+
+
+@pytest.mark.parametrize("shape", [(8, 2, 64), (16, 1, 64), (5, 1, 64), (12, 4, 128), (16, 1, 128), (3, 1, 128)])
+def test_attention_head_shapes(gpu, shape):
+    """Group sizes 1, 3, 4, 5, 16 and both head sizes on a ragged batch with split key ranges allowed."""
+    Hq, Hkv, D = shape
+    cfg = Config(97, "fp8 shapes", 31 + Hq, 5, Hq, Hkv, D, 40, ("uniform", 1, 300), ("lognormal", 120, 0.9, 1, 500))
+    ep = build_episode(cfg, threads=2)
+    ks, vs = amax_scale(ep.k), amax_scale(ep.v)
+    chunks = uniform_chunks(ep.prompt_len, ep.resp_len, cfg.chunk)
+    se = run_gpu(gpu, ep, chunks, ks, vs)
+    cache, ref = oracle_run(ep, chunks, se.slot_begin, ks, vs)
+    check_codes(se, cache)
+    check_outputs(se, ref, f"fp8 shape {shape}")
 
 
 @pytest.mark.timeout(900)
