@@ -297,8 +297,8 @@ int oppo_kv_append_fp8(const oppo_attn_desc* desc, oppo_kv_cache_fp8* cache,
  * exact attention over the stored values by the rounding of queries and weights - a few
  * percent of a value's magnitude per element for short rows, less for long ones - on top
  * of the error of storing K and V in 8 bits.  Workspace rules as oppo_chunk_prefill_attn.
- * Errors: as oppo_chunk_prefill_attn; INVALID for bad scales or slab starts that are not
- * multiples of 64.
+ * Errors: as oppo_chunk_prefill_attn; INVALID for bad scales (softmax_scale x k_scale must
+ * lie within 2^-100 .. 2^100) or slab starts that are not multiples of 64.
  */
 int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_fp8* cache,
                                 const int32_t* cu_q /* host [batch+1] */,

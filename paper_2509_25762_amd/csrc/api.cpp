@@ -828,6 +828,10 @@ int oppo_chunk_prefill_attn_fp8(const oppo_attn_desc* desc, const oppo_kv_cache_
   ls.fp8 = 1;
   ls.c *= cache->k_scale;
   ls.out_scale = cache->v_scale;
+  // (the kernel splits the score factor into a power of two, which it hands to the matrix instruction as a
+  // block scale, and a factor in [4, 8): the exponent has to be representable there)
+  if (!(ls.c >= 0x1p-100f) || !(ls.c <= 0x1p100f))
+    return fail(OPPO_ERR_INVALID, "softmax_scale x k_scale = %g is outside 2^-100 .. 2^100", (double)ls.c / 1.4426950408889634);
   return run_attention(opt, ls, seqs, q, view.k, view.v, nullptr, nullptr, out, workspace, workspace_bytes, stream, true);
 }
 

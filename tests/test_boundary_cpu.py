@@ -536,6 +536,9 @@ def test_fp8_cache_validation_leaves_lengths_untouched(lib):
             ob.oppo_chunk_prefill_attn_fp8(desc, bad, [0, 1, 0 + 1], 0x3000, 0x4000, stream=0)
         assert e.value.code == ob.OPPO_ERR_INVALID
         assert bad.kv_len.tolist() == [100, 0]
+    with pytest.raises(ob.OppoError) as e:                       # a score factor the kernel cannot split
+        ob.oppo_chunk_prefill_attn_fp8(desc, cache(ks=1e-36), [0, 1, 1], 0x3000, 0x4000, stream=0)
+    assert e.value.code == ob.OPPO_ERR_INVALID
     with pytest.raises(ob.OppoError) as e:                       # rows that were never appended
         ob.oppo_chunk_prefill_attn_fp8(desc, c, [0, 101, 101], 0x3000, 0x4000, stream=0)
     assert e.value.code == ob.OPPO_ERR_INVALID
