@@ -585,7 +585,65 @@ def qkv_proj_measure(args, cfg, torch, ob, only_fused=False):
     return res, workload, steps, warmup
 
 
+def qkv_proj_rows_sweep(args, cfg, torch, ob) -> int:
+    """Fused projection against library GEMM + oppo_qkv_rope_append for passes of 256 .. 16384 rows (uniform
+    sequences of 256 new rows on empty caches, the configuration's head shape, hidden = Hq * D): the pass sizes
+    a streamed episode goes through as its batch thins out.  The launch picks its tile height per pass."""
+    dev = torch.device("cuda:0")
+    Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+    hidden, n_out, C = Hq * D, (Hq + 2 * Hkv) * D, 256
+    desc = ob.make_desc(Hq, Hkv, D, cfg.softmax_scale)
+    w = (torch.randn((n_out, hidden), device=dev, dtype=torch.float32) / np.sqrt(hidden)).to(torch.bfloat16)
+    out = []
+    for B in (1, 2, 4, 8, 16, 32, 64):
+        rows = B * C
+        P = np.zeros(B, dtype=np.int32)
+        cu = (np.arange(B + 1) * C).astype(np.int32)
+        ck = torch.zeros((rows, Hkv, D), device=dev, dtype=torch.int16)
+        cache = ob.KVCache(ck, torch.zeros_like(ck), np.arange(B + 1, dtype=np.int64) * C, P)
+        q_out = torch.empty((rows, Hq, D), device=dev, dtype=torch.int16)
+        y = torch.empty((rows, n_out), device=dev, dtype=torch.bfloat16)
+        xs = [torch.randn((rows, hidden), device=dev, dtype=torch.bfloat16) for _ in range(3)]
+        ws = torch.empty(ob.oppo_qkv_proj_workspace_bytes(desc, rows), dtype=torch.uint8, device=dev)
+
+        def fused(i):
+            cache.kv_len[:] = P
+            ob.oppo_qkv_proj_rope_append(desc, cache, cu, xs[i % 3].view(torch.int16), hidden, w.view(torch.int16), q_out, ws)
+
+        def library(i):
+            cache.kv_len[:] = P
+            torch.matmul(xs[i % 3], w.t(), out=y)
+            ob.oppo_qkv_rope_append(desc, cache, cu, y.view(torch.int16).view(rows, Hq + 2 * Hkv, D), q_out)
+
+        row = {"rows": rows}
+        for name, fn in (("fused_ms", fused), ("library_gemm_then_rope_append_ms", library)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            done, total = 0, 0.0
+            while total < SETTLE_MS / 2:
+                e0.record()
+                for _ in range(20):
+                    fn(done)
+                    done += 1
+                e1.record()
+                e1.synchronize()
+                total += e0.elapsed_time(e1)
+            e0.record()
+            for i in range(50):
+                fn(done + i)
+            e1.record()
+            torch.cuda.synchronize()
+            row[name] = e0.elapsed_time(e1) / 50
+        row["fused_tflops"] = 2.0 * rows * hidden * n_out / (row["fused_ms"] * 1e-3) / 1e12
+        out.append(row)
+    print(json.dumps({"metric": "fused QKV projection over pass sizes", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"passes of 256 new rows per sequence, hidden {hidden} -> ({Hq} + 2 x {Hkv}) heads x {D}"},
+                      "passes": out}))
+    return 0
+
+
 def qkv_proj_bench(args, cfg, torch, ob) -> int:
+    if args.rows_sweep:
+        return qkv_proj_rows_sweep(args, cfg, torch, ob)
     res, workload, steps, warmup = qkv_proj_measure(args, cfg, torch, ob)
     f = res["fused_projection_rope_append"]
     print(json.dumps({"metric": "fused QKV projection with rotary / cache epilogue", "value": f["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
@@ -981,6 +1039,8 @@ def main() -> int:
     ap.add_argument("--qkv-proj", action="store_true",
                     help="time the fused QKV projection with its rotary / cache epilogue (oppo_qkv_proj_rope_append) on the "
                          "workload's first response pass, next to the vendor library's GEMM followed by oppo_qkv_rope_append")
+    ap.add_argument("--rows-sweep", action="store_true",
+                    help="with --qkv-proj: passes of 256 .. 16384 rows instead of the workload's first pass")
     ap.add_argument("--layer-path", action="store_true",
                     help="the streamed episode with the rotary embedding included, two ways: oppo_rope + oppo_chunk_step, "
                          "and oppo_qkv_rope_append + oppo_chunk_prefill_attn")

@@ -94,6 +94,40 @@ def test_projection_epilogue_matches_the_oracle_on_a_ragged_pass(gpu, Hq, Hkv, D
     assert differ <= max(4, gq[1:-1].size // 200), f"{differ} of {gq[1:-1].size} query elements differ from the rounded oracle value"
 
 
+@pytest.mark.parametrize("rows", [4091, 8155])
+def test_larger_passes_take_the_larger_tiles(gpu, rows):
+    """The launch picks the tile height from the pass's size: 64 rows for the thin passes above, 128 rows for
+    ~4K rows x 6 column tiles and 256 rows for ~8K (the estimate in launch_qkv_proj); both with a ragged last
+    row tile and sequences of uneven length, against the oracle as above."""
+    Hq, Hkv, D, hidden, base = 8, 2, 128, 256, 10000.0
+    rng = np.random.default_rng(900 + rows)
+    q_len = np.array([rows // 2, 1, rows // 4 + 3, 0, 517], dtype=np.int32)
+    q_len = np.append(q_len, rows - q_len.sum()).astype(np.int32)
+    assert (q_len >= 0).all() and q_len.sum() == rows
+    kv_before = np.array([3, 70000, 0, 9, 255, 1024], dtype=np.int32)
+    xb, wb, cu, slot_begin, cache, gq, gk, gv = run_projection(gpu, rng, Hq, Hkv, D, hidden, kv_before, q_len, base)
+    q_ref, k_ref, v_ref = qkv_projection_rope(xb, wb, pass_positions(kv_before, q_len), Hq, Hkv, D, base)
+    mag = np.abs(bf16_bits_to_f64(xb)) @ np.abs(bf16_bits_to_f64(wb)).T
+    qc, kc, half = Hq * D, Hkv * D, D // 2
+
+    def pair(m, heads):
+        m = m.reshape(m.shape[0], heads, D)
+        p = m[..., :half] + m[..., half:]
+        return np.concatenate([p, p], axis=-1)
+
+    assert (gq[0] == 0x7FC0).all() and (gq[-1] == 0x7FC0).all(), "rows outside the pass were written"
+    assert (np.abs(bf16_bits_to_f64(gq[1:-1]) - q_ref) <= bound_of(q_ref, pair(mag[:, :qc], Hq))).all(), "queries"
+    assert cache.kv_len.tolist() == (kv_before + q_len).tolist()
+    for i in range(len(q_len)):
+        b, n0, n1 = int(slot_begin[i]), int(kv_before[i]), int(kv_before[i] + q_len[i])
+        r0, r1 = int(cu[i]), int(cu[i + 1])
+        got_k, got_v = bf16_bits_to_f64(gk[b + n0:b + n1]), bf16_bits_to_f64(gv[b + n0:b + n1])
+        assert (np.abs(got_k - k_ref[r0:r1]) <= bound_of(k_ref[r0:r1], pair(mag[r0:r1, qc:qc + kc], Hkv))).all(), f"keys of sequence {i}"
+        assert (np.abs(got_v - v_ref[r0:r1]) <= bound_of(v_ref[r0:r1], mag[r0:r1, qc + kc:].reshape(r1 - r0, Hkv, D))).all(), f"values of sequence {i}"
+        assert (gk[b:b + n0] == 0xFFFF).all() and (gk[b + n1:int(slot_begin[i + 1])] == 0xFFFF).all()
+        assert (gv[b:b + n0] == 0xFFFF).all() and (gv[b + n1:int(slot_begin[i + 1])] == 0xFFFF).all()
+
+
 def test_values_are_the_rounded_fp32_sums_when_products_are_exact(gpu):
     """Small integers: every product and partial sum is exact in fp32, so value heads (no rotation) and
     the rows at position 0 (rotation by 0) must be bit-exact, whatever the order of accumulation."""
