@@ -58,7 +58,7 @@ def bound_of(want, mag):
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,hidden,base", [(8, 2, 128, 256, 10000.0), (4, 4, 64, 128, 500000.0), (3, 1, 64, 1024, 10000.0),
-                                                   (16, 1, 128, 512, 1000000.0)])
+                                                   (16, 1, 128, 512, 1000000.0), (2, 1, 64, 64, 10000.0)])   # the last: one k tile
 def test_projection_epilogue_matches_the_oracle_on_a_ragged_pass(gpu, Hq, Hkv, D, hidden, base):
     rng = np.random.default_rng(300 + Hq + D + hidden)
     q_len = np.array([0, 1, 7, 64, 130, 9, 0, 33, 129], dtype=np.int32)          # 373 rows: three row tiles, a ragged last one
